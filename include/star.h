@@ -1,0 +1,170 @@
+/*
+ * libstar -- group-synchronous parameter update of STAR (arXiv 2512.09685) on
+ * one MI355X (gfx950).
+ *
+ * A parameter server holds one shard of the parameters.  Each parameter
+ * update is fed by a *worker group*: all workers (SSGD), any one worker
+ * (ASGD), x workers (static x-order mode) or one cluster of workers with
+ * similar iteration times (dynamic x-order mode) -- Section 1 items (2) and
+ * (4), Section 4.2.  The server aggregates the group's gradient copies and
+ * updates its parameter copy (Section 2, parameter-server description).  This
+ * library runs a stream of U such updates over one shard of P parameters in a
+ * single pass over HBM.
+ *
+ * One update u with group G_u (y_u distinct worker ids), on every element j:
+ *     gbar_u[j] = sum_{w in G_u} c_{u,w} * g_w[j]
+ *     d         = gbar_u[j] + weight_decay * p[j]
+ *     v[j]      = momentum * v[j] + d
+ *     p[j]      = p[j] - lr_u * v[j]
+ * (the SGD of PyTorch, the framework the paper names in Section 5.1:
+ * dampening 0, no Nesterov, decay coupled into the gradient), and optionally
+ *     norms_out[u] = || gbar_u ||_2        (before weight decay)
+ * the per-group gradient norm (gradient-norm progress signal, Sections 4.3.1
+ * and 7).  c_{u,w} = 1/y_u (STAR_W_MEAN), 1/(y_u (1+s_{u,w})) with staleness
+ * s (STAR_W_STALE, not renormalised) or a caller-given value (STAR_W_EXPLICIT).
+ * With scale_lr_by_group the rate of update u is lr_u * y_u / W: the learning
+ * rate scaled in proportion to the number of gradient reports (Section 4.3.1,
+ * "Scaling learning rate after switching").
+ *
+ * Arithmetic on the device is fp32 with fused multiply-add, members summed in
+ * ascending worker id; gradients may be fp32 or bf16 (widened exactly to
+ * fp32).  Results do not depend on the order in which a group lists its
+ * members and are bitwise reproducible from run to run.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers ordinary host memory.  The caller owns every buffer; the
+ *     library neither frees nor keeps them.  Host arrays and structs are
+ *     consumed before the call returns.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
+ *     the call does not wait for it.  Outputs are valid after the stream has
+ *     been synchronised.
+ *   - The return value is a star_status.  Nothing is thrown, nothing aborts.
+ *     All argument checks precede the first enqueue: on a status other than
+ *     STAR_OK and STAR_ERR_DEVICE no device memory has been modified.
+ *   - P == 0 or U == 0 is a valid no-op (norms of an empty shard are 0).
+ *   - Gradient rows may alias each other; they must not alias params,
+ *     momentum or norms_out.  Rows are read-only during the call.
+ *   - Any alignment is accepted; when params, momentum and all rows are
+ *     16-byte aligned the vector path is used, otherwise an element-wise path
+ *     with the same arithmetic (identical results).
+ *   - The library keeps a small internal workspace (coefficient tables,
+ *     per-block norm partials), created on first use, released by
+ *     star_shutdown().  Calls may come from several host threads.
+ */
+#ifndef STAR_H
+#define STAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STAR_MAX_WORKERS 32
+
+typedef enum {
+    STAR_OK = 0,
+    STAR_ERR_NULL = 1,   /* a required pointer is NULL                                        */
+    STAR_ERR_SHAPE = 2,  /* P < 0, W < 1, W > STAR_MAX_WORKERS, U < 0                          */
+    STAR_ERR_GROUP = 3,  /* empty group, id outside [0,W), duplicate id, offsets not monotone  */
+    STAR_ERR_HPARAM = 4, /* non-finite lr / momentum / weight decay / coefficient, negative
+                            staleness, unknown weighting mode                                   */
+    STAR_ERR_DTYPE = 5,  /* unknown gradient dtype                                             */
+    STAR_ERR_KERNEL = 6, /* unknown kernel choice in star_set_kernel / STAR_KERNEL             */
+    STAR_ERR_DEVICE = 7  /* a HIP call failed; text via star_last_error()                      */
+} star_status;
+
+typedef enum { STAR_F32 = 0, STAR_BF16 = 1 } star_dtype;
+
+typedef enum {
+    STAR_W_MEAN = 0,    /* c = 1/y                    */
+    STAR_W_STALE = 1,   /* c = 1/(y (1+s))            */
+    STAR_W_EXPLICIT = 2 /* c = coeff[] as given       */
+} star_wmode;
+
+/* How the U updates are evaluated on the device (both give the same result up
+ * to fp32 rounding; see star_plan_affine). */
+typedef enum {
+    STAR_KERNEL_AUTO = 0,  /* pick by arithmetic cost                                          */
+    STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
+    STAR_KERNEL_AFFINE = 2 /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1) */
+} star_kernel;
+
+/* The stream of updates of one call (all arrays on the host).  Group u is
+ * members[offsets[u] .. offsets[u+1]).  (Worker group: Section 1 item (4).) */
+typedef struct {
+    int32_t U;
+    const int32_t *offsets;   /* [U+1], offsets[0] == 0, strictly increasing            */
+    const int32_t *members;   /* [offsets[U]] worker ids in [0, W)                      */
+    const int32_t *staleness; /* [offsets[U]] or NULL (= all 0); used by STAR_W_STALE   */
+    const float *coeff;       /* [offsets[U]]; required by, and only used by, STAR_W_EXPLICIT */
+    const float *lr;          /* [U] learning rate of each update, or NULL -> hp.lr     */
+} star_updates;
+
+typedef struct {
+    float lr;                  /* used when star_updates.lr is NULL                      */
+    float momentum;
+    float weight_decay;
+    int32_t wmode;             /* star_wmode                                             */
+    int32_t scale_lr_by_group; /* nonzero: lr_u *= y_u / W  (Section 4.3.1)              */
+} star_hparams;
+
+/*
+ * Run U group updates on one shard (Sections 1, 2, 4.2; formulas above).
+ *   params, momentum : device, float[P], updated in place.
+ *   grad_rows        : host array of W device pointers; row w holds worker w's
+ *                      gradient for this shard, P elements of grad_dtype.
+ *                      Rows no group references are never read (may be NULL).
+ *   norms_out        : device float[U], or NULL when norms are not wanted.
+ */
+star_status star_group_update(float *params, float *momentum, const void *const *grad_rows,
+                              star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
+                              const star_hparams *hp, float *norms_out, void *hip_stream);
+
+/*
+ * Per-group gradient norms only: norms_out[u] = || sum_w c_{u,w} g_w ||_2
+ * (gradient-norm signal, Sections 4.3.1 and 7).  Arguments as above; wmode is
+ * a star_wmode.  No parameter state is read or written.
+ */
+star_status star_group_norms(const void *const *grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                             const star_updates *upd, int32_t wmode, float *norms_out, void *hip_stream);
+
+/*
+ * Host-only: the U updates of a stream written as one affine map,
+ *     (p_U, v_U)^T = M (p_0, v_0)^T + B (g_0 .. g_{W-1})^T,
+ * composed in double precision.  M is row-major 2x2, B row-major 2xW.  Touches
+ * no device.  This is what STAR_KERNEL_AFFINE evaluates (after rounding the
+ * entries to fp32, M[0] as M[0]-1).  Same validation and status codes as
+ * star_group_update.
+ */
+star_status star_plan_affine(int32_t W, const star_updates *upd, const star_hparams *hp, double M[4], double *B);
+
+/*
+ * Host-only: which evaluation star_group_update would use for this stream
+ * (STAR_KERNEL_SEQ or STAR_KERNEL_AFFINE), and optionally the fused
+ * multiply-adds per element of each (either pointer may be NULL).
+ */
+star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hparams *hp, int32_t want_norms,
+                             int32_t *kernel_out, double *fma_seq, double *fma_affine);
+
+/* Force an evaluation for later calls of this process (default AUTO; the
+ * environment variable STAR_KERNEL=auto|seq|affine sets the initial value). */
+star_status star_set_kernel(int32_t kernel);
+
+/* Bytes of internal device workspace one call of this shape uses. */
+size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U);
+
+/* Text of the last error on the calling thread ("" if none). Never NULL. */
+const char *star_last_error(void);
+
+const char *star_version(void);
+
+/* Waits for the library's own pending work and frees its workspace. */
+void star_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAR_H */

@@ -1,0 +1,11 @@
+"""MI355X-native group-synchronous parameter update of STAR (arXiv 2512.09685).
+
+The product is ``libstar.so`` (C ABI, declared in ``include/star.h``); this
+package is its thin Python binding.  PyTorch only supplies device memory and
+streams.
+"""
+from .binding import (  # noqa: F401
+    KERNEL_AFFINE, KERNEL_AUTO, KERNEL_SEQ, StarError, UpdateStream, last_error, library_path, load_library,
+    star_group_norms, star_group_update, star_plan_affine, star_plan_choice, star_set_kernel, star_shutdown,
+    star_version, star_workspace_bytes,
+)

@@ -1,0 +1,211 @@
+"""ctypes binding of libstar.so: argument marshalling only.
+
+Functions carry the names of the C entry points (``include/star.h``).  Tensors
+are only asked for their ``data_ptr()``; the stream is passed as its raw
+handle.  There is no fallback: if the library is missing or was not built, the
+import of this module's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libstar.so")
+
+KERNEL_AUTO, KERNEL_SEQ, KERNEL_AFFINE = 0, 1, 2
+F32, BF16 = 0, 1
+_WMODES = {"mean": 0, "stale": 1, "explicit": 2}
+STATUS_NAMES = {0: "STAR_OK", 1: "STAR_ERR_NULL", 2: "STAR_ERR_SHAPE", 3: "STAR_ERR_GROUP", 4: "STAR_ERR_HPARAM",
+                5: "STAR_ERR_DTYPE", 6: "STAR_ERR_KERNEL", 7: "STAR_ERR_DEVICE"}
+
+
+class StarError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+class _Updates(ctypes.Structure):
+    _fields_ = [("U", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("members", ctypes.c_void_p),
+                ("staleness", ctypes.c_void_p), ("coeff", ctypes.c_void_p), ("lr", ctypes.c_void_p)]
+
+
+class _HParams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("wmode", ctypes.c_int32), ("scale_lr_by_group", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libstar.so.  Builds it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build_library(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.star_group_update.restype = ctypes.c_int
+    lib.star_group_update.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp]
+    lib.star_group_norms.restype = ctypes.c_int
+    lib.star_group_norms.argtypes = [vp, ctypes.c_int, i64, i32, vp, i32, vp, vp]
+    lib.star_plan_affine.restype = ctypes.c_int
+    lib.star_plan_affine.argtypes = [i32, vp, vp, vp, vp]
+    lib.star_plan_choice.restype = ctypes.c_int
+    lib.star_plan_choice.argtypes = [i32, vp, vp, i32, vp, vp, vp]
+    lib.star_set_kernel.restype = ctypes.c_int
+    lib.star_set_kernel.argtypes = [i32]
+    lib.star_workspace_bytes.restype = ctypes.c_size_t
+    lib.star_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.star_last_error.restype = ctypes.c_char_p
+    lib.star_version.restype = ctypes.c_char_p
+    lib.star_shutdown.restype = None
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load_library().star_last_error().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise StarError(status, last_error())
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+class UpdateStream:
+    """Host-side stream of U worker groups (``star_updates`` of the C header)."""
+
+    def __init__(self, offsets, members, staleness=None, coeff=None, lr=None):
+        self.offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+        self.members = np.ascontiguousarray(members, dtype=np.int32)
+        self.staleness = None if staleness is None else np.ascontiguousarray(staleness, dtype=np.int32)
+        self.coeff = None if coeff is None else np.ascontiguousarray(coeff, dtype=np.float32)
+        self.lr = None if lr is None else np.ascontiguousarray(lr, dtype=np.float32)
+        self.U = int(self.offsets.shape[0]) - 1
+        self.c = _Updates(self.U, _np_ptr(self.offsets), _np_ptr(self.members), _np_ptr(self.staleness),
+                          _np_ptr(self.coeff), _np_ptr(self.lr))
+
+
+def _hparams(lr, momentum, weight_decay, wmode, scale_lr_by_group):
+    return _HParams(float(lr), float(momentum), float(weight_decay), _WMODES[wmode] if isinstance(wmode, str) else wmode,
+                    int(bool(scale_lr_by_group)))
+
+
+def _rows(grad_rows: Sequence, P: int):
+    """(host array of device pointers, dtype code) for a list of 1-D tensors."""
+    import torch
+    W = len(grad_rows)
+    ptrs = (ctypes.c_void_p * max(W, 1))()
+    dt = None
+    for w, r in enumerate(grad_rows):
+        if r is None:
+            ptrs[w] = None
+            continue
+        if r.dtype == torch.float32:
+            d = F32
+        elif r.dtype == torch.bfloat16:
+            d = BF16
+        else:
+            raise TypeError("gradient rows must be float32 or bfloat16 tensors")
+        if dt is not None and d != dt:
+            raise TypeError("all gradient rows must share one dtype")
+        dt = d
+        if not r.is_contiguous() or r.dim() != 1 or r.shape[0] != P:
+            raise ValueError("every gradient row must be a contiguous 1-D tensor of the shard's length")
+        ptrs[w] = r.data_ptr()
+    return ptrs, (F32 if dt is None else dt)
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStream, *, lr: float, momentum_coef: float,
+                      weight_decay: float = 0.0, wmode="mean", scale_lr_by_group: bool = False, norms_out=None,
+                      stream=None) -> None:
+    """U group updates of one shard, in place, enqueued on ``stream``
+    (default: torch's current stream).  ``params``/``momentum``: float32 CUDA
+    tensors [P]; ``grad_rows``: W tensors [P] (float32 or bfloat16);
+    ``norms_out``: float32 CUDA tensor [U] or None."""
+    lib = load_library()
+    P = int(params.shape[0])
+    if not (params.is_contiguous() and momentum.is_contiguous()) or momentum.shape[0] != P:
+        raise ValueError("params and momentum must be contiguous and of equal length")
+    ptrs, dt = _rows(grad_rows, P)
+    hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
+    if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
+        raise ValueError("norms_out must hold U floats")
+    _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                 ctypes.byref(updates.c), ctypes.byref(hp),
+                                 None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
+
+
+def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, wmode="mean", stream=None) -> None:
+    lib = load_library()
+    P = int(next(r for r in grad_rows if r is not None).shape[0])
+    ptrs, dt = _rows(grad_rows, P)
+    if norms_out.shape[0] < updates.U or not norms_out.is_contiguous():
+        raise ValueError("norms_out must hold U floats")
+    _check(lib.star_group_norms(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c),
+                                _WMODES[wmode] if isinstance(wmode, str) else wmode, norms_out.data_ptr(),
+                                _stream_handle(stream)))
+
+
+def star_plan_affine(W: int, updates: UpdateStream, *, lr: float, momentum_coef: float, weight_decay: float = 0.0,
+                     wmode="mean", scale_lr_by_group: bool = False):
+    """Host-only: (M [2,2], B [2,W]) of the collapsed map, float64."""
+    lib = load_library()
+    hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
+    M = np.zeros(4, dtype=np.float64)
+    B = np.zeros(2 * max(W, 1), dtype=np.float64)
+    _check(lib.star_plan_affine(W, ctypes.byref(updates.c), ctypes.byref(hp), _np_ptr(M), _np_ptr(B)))
+    return M.reshape(2, 2), B[:2 * W].reshape(2, W)
+
+
+def star_plan_choice(W: int, updates: UpdateStream, *, lr: float, momentum_coef: float, weight_decay: float = 0.0,
+                     wmode="mean", scale_lr_by_group: bool = False, want_norms: bool = False):
+    """Host-only: (kernel, fma_seq, fma_affine)."""
+    lib = load_library()
+    hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
+    k = ctypes.c_int32(0)
+    a, b = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib.star_plan_choice(W, ctypes.byref(updates.c), ctypes.byref(hp), int(want_norms), ctypes.byref(k),
+                                ctypes.byref(a), ctypes.byref(b)))
+    return k.value, a.value, b.value
+
+
+def star_set_kernel(kernel: int) -> None:
+    _check(load_library().star_set_kernel(kernel))
+
+
+def star_workspace_bytes(P: int, W: int, U: int) -> int:
+    return int(load_library().star_workspace_bytes(P, W, U))
+
+
+def star_version() -> str:
+    return load_library().star_version().decode()
+
+
+def star_shutdown() -> None:
+    load_library().star_shutdown()

@@ -1,0 +1,378 @@
+// C-ABI layer of libstar: argument checks, planning, workspace, launches.
+// Every step of the update itself runs in the kernels of star_kernels.hip.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "star.h"
+#include "star_kernels.h"
+#include "star_plan.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+star_status set_err(star_status s, const std::string& msg) {
+    g_err = msg;
+    return s;
+}
+
+star_status hip_fail(hipError_t e, const char* what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return STAR_ERR_DEVICE;
+}
+
+#define STAR_HIP(call)                                         \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);      \
+    } while (0)
+
+int initial_kernel_choice() {
+    const char* e = std::getenv("STAR_KERNEL");
+    if (!e) return STAR_KERNEL_AUTO;
+    if (!std::strcmp(e, "seq")) return STAR_KERNEL_SEQ;
+    if (!std::strcmp(e, "affine")) return STAR_KERNEL_AFFINE;
+    return STAR_KERNEL_AUTO;
+}
+
+int g_kernel_choice = initial_kernel_choice();
+
+// ---------------------------------------------------------------- workspace
+// A ring of slots.  One call uses one slot: a pinned host staging buffer and a
+// device buffer for the tables, a device buffer for the per-block partial sums
+// and the reduced Gram matrix.  A slot's event is recorded after the last
+// kernel that touches it; the slot is handed out again only once that event
+// has completed, so calls on different streams never share live memory.
+struct Slot {
+    int device = -1;
+    void* host = nullptr;     // pinned
+    void* dev = nullptr;      // tables
+    size_t table_cap = 0;
+    double* partials = nullptr;
+    size_t partial_cap = 0;   // doubles
+    hipEvent_t done = nullptr;
+    bool used = false;
+};
+
+constexpr int kSlots = 8;
+Slot g_slots[kSlots];
+int g_next_slot = 0;
+std::mutex g_mu;
+
+struct DeviceInfo {
+    int device = -1;
+    int num_cu = 0;
+};
+DeviceInfo g_dev[16];
+
+star_status device_info(int* device, int* num_cu) {
+    STAR_HIP(hipGetDevice(device));
+    if (*device < 0 || *device >= 16) return set_err(STAR_ERR_DEVICE, "device index out of range");
+    DeviceInfo& d = g_dev[*device];
+    if (d.device != *device) {
+        int n = 0;
+        STAR_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, *device));
+        d.num_cu = n > 0 ? n : 1;
+        d.device = *device;
+    }
+    *num_cu = d.num_cu;
+    return STAR_OK;
+}
+
+void free_slot(Slot& s) {
+    if (s.done) {
+        (void)hipEventSynchronize(s.done);
+        (void)hipEventDestroy(s.done);
+    }
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.dev) (void)hipFree(s.dev);
+    if (s.partials) (void)hipFree(s.partials);
+    s = Slot();
+}
+
+// Hands out the next slot with at least the asked capacities (g_mu held).
+star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles, Slot** out) {
+    Slot& s = g_slots[g_next_slot];
+    g_next_slot = (g_next_slot + 1) % kSlots;
+    if (s.used && s.device != device) free_slot(s);
+    if (s.used) STAR_HIP(hipEventSynchronize(s.done));
+    if (!s.done) STAR_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    s.device = device;
+    s.used = true;
+    if (table_bytes > s.table_cap) {
+        if (s.host) STAR_HIP(hipHostFree(s.host));
+        if (s.dev) STAR_HIP(hipFree(s.dev));
+        s.host = s.dev = nullptr;
+        s.table_cap = 0;
+        const size_t cap = std::max<size_t>(table_bytes, 64 * 1024);
+        STAR_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        STAR_HIP(hipMalloc(&s.dev, cap));
+        s.table_cap = cap;
+    }
+    if (partial_doubles > s.partial_cap) {
+        if (s.partials) STAR_HIP(hipFree(s.partials));
+        s.partials = nullptr;
+        s.partial_cap = 0;
+        STAR_HIP(hipMalloc(reinterpret_cast<void**>(&s.partials), partial_doubles * sizeof(double)));
+        s.partial_cap = partial_doubles;
+    }
+    *out = &s;
+    return STAR_OK;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Table layout in a slot (all offsets 256-byte aligned):
+//   coef_f32 [U][Wp] | lr_f32 [U] | mask_u32 [U] | coef_f64 [U][Wp]
+struct TableLayout {
+    size_t coef32, lr32, mask, coef64, total;
+};
+
+TableLayout table_layout(int U, int Wp) {
+    TableLayout t;
+    size_t o = 0;
+    t.coef32 = o; o = align_up(o + sizeof(float) * (size_t)U * Wp, 256);
+    t.lr32 = o;   o = align_up(o + sizeof(float) * (size_t)U, 256);
+    t.mask = o;   o = align_up(o + sizeof(uint32_t) * (size_t)U, 256);
+    t.coef64 = o; o = align_up(o + sizeof(double) * (size_t)U * Wp, 256);
+    t.total = o;
+    return t;
+}
+
+size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
+    const size_t ng = (size_t)Wp * (Wp + 1) / 2;
+    const size_t useq = (size_t)std::min(U, star::seq_max_updates(Wp, true));
+    // per-block partials of the larger of the two routes, plus the reduced Gram matrix
+    return std::max(ng, useq) * (size_t)grid_cap + ng;
+}
+
+// The shared body of star_group_update (update = true) and star_group_norms.
+star_status run(bool update, float* params, float* momentum, const void* const* grad_rows, int grad_dtype,
+                int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode,
+                float* norms_out, void* hip_stream) {
+    g_err.clear();
+    if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
+    if (update && !hp) return set_err(STAR_ERR_NULL, "hyper-parameter struct is NULL");
+    if (!update && !norms_out) return set_err(STAR_ERR_NULL, "norms_out is NULL");
+    if (!grad_rows) return set_err(STAR_ERR_NULL, "grad_rows is NULL");
+    if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
+    if (update && P > 0 && (!params || !momentum)) return set_err(STAR_ERR_NULL, "params or momentum is NULL");
+    if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
+
+    const bool want_norms = norms_out != nullptr;
+    star::Plan plan;
+    std::string msg;
+    star_status st = star::build_plan(W, upd, update ? hp : nullptr, wmode, want_norms, &plan, &msg);
+    if (st != STAR_OK) return set_err(st, msg);
+    const int U = plan.U, Wc = plan.Wc;
+    if (P > 0)
+        for (int k = 0; k < Wc; ++k)
+            if (!grad_rows[plan.row_of[k]]) return set_err(STAR_ERR_NULL, "a gradient row used by a group is NULL");
+    if (U == 0) return STAR_OK;
+
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (P == 0) {
+        if (want_norms) STAR_HIP(star::launch_fill(norms_out, U, 0.0f, stream));
+        return STAR_OK;
+    }
+
+    int device = 0, num_cu = 1;
+    st = device_info(&device, &num_cu);
+    if (st != STAR_OK) return st;
+    const int grid_cap = num_cu * star::kMaxBlocksPerCU;
+
+    const int grad_bytes = grad_dtype == STAR_F32 ? 4 : 2;
+    const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice);
+    const int Wp = star::padded_rows(Wc);
+
+    // rows in compact order; padding rows repeat the last row with zero coefficients
+    star::RowPtrs rows;
+    bool vec_ok = !update || (aligned16(params) && aligned16(momentum));
+    for (int k = 0; k < STAR_MAX_WORKERS; ++k) {
+        rows.p[k] = grad_rows[plan.row_of[std::min(k, Wc - 1)]];
+        if (k < Wc && !aligned16(rows.p[k])) vec_ok = false;
+    }
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    const TableLayout lay = table_layout(U, Wp);
+    Slot* slot = nullptr;
+    st = acquire_slot(device, lay.total, want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
+    if (st != STAR_OK) return st;
+
+    const bool need_seq_tables = route != star::Route::Affine;
+    const bool need_gram_coef = want_norms && route == star::Route::Affine;
+    char* h = static_cast<char*>(slot->host);
+    char* d = static_cast<char*>(slot->dev);
+    if (need_seq_tables) {
+        float* c32 = reinterpret_cast<float*>(h + lay.coef32);
+        float* l32 = reinterpret_cast<float*>(h + lay.lr32);
+        uint32_t* mk = reinterpret_cast<uint32_t*>(h + lay.mask);
+        for (int u = 0; u < U; ++u) {
+            for (int k = 0; k < Wp; ++k) c32[(size_t)u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
+            l32[u] = (float)plan.lr[u];
+            mk[u] = plan.mask[u];
+        }
+    }
+    if (need_gram_coef) {
+        double* c64 = reinterpret_cast<double*>(h + lay.coef64);
+        for (int u = 0; u < U; ++u)
+            for (int k = 0; k < Wp; ++k) c64[(size_t)u * Wp + k] = k < Wc ? plan.coef[(size_t)u * Wc + k] : 0.0;
+    }
+    if (need_seq_tables || need_gram_coef) {
+        const size_t lo = need_seq_tables ? 0 : lay.coef64;
+        const size_t hi = need_gram_coef ? lay.total : lay.coef64;
+        STAR_HIP(hipMemcpyAsync(d + lo, h + lo, hi - lo, hipMemcpyHostToDevice, stream));
+    }
+
+    hipError_t e = hipSuccess;
+    int grid = 0;
+    // collapsed update (with or without the Gram matrix)
+    if (route == star::Route::Affine || route == star::Route::AffinePlusDirectNorms) {
+        const bool gram = want_norms && route == star::Route::Affine;
+        if (update || gram) {
+            star::AffArgs a;
+            a.params = params;
+            a.momentum = momentum;
+            a.rows = rows;
+            std::memset(&a.cf, 0, sizeof a.cf);
+            if (update) {
+                a.cf.dp = (float)(plan.M[0] - 1.0);
+                a.cf.m01 = (float)plan.M[1];
+                a.cf.m10 = (float)plan.M[2];
+                a.cf.m11 = (float)plan.M[3];
+                for (int k = 0; k < Wc; ++k) {
+                    a.cf.b0[k] = (float)plan.B[k];
+                    a.cf.b1[k] = (float)plan.B[Wc + k];
+                }
+            }
+            a.P = P;
+            a.vec_ok = vec_ok ? 1 : 0;
+            a.partials = slot->partials;
+            e = star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
+            if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
+            if (gram) {
+                const int ng = Wp * (Wp + 1) / 2;
+                double* gamma = slot->partials + (size_t)ng * grid;
+                e = star::launch_reduce(slot->partials, ng, grid, gamma, nullptr, stream);
+                if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
+                e = star::launch_gram_norms(gamma, reinterpret_cast<const double*>(d + lay.coef64), U, Wp, norms_out,
+                                            stream);
+                if (e != hipSuccess) return hip_fail(e, "launch of the norm kernel");
+            }
+        }
+    }
+    // step-by-step evaluation: everything (Seq), or only the norms after a collapsed update
+    if (route == star::Route::Seq || (route == star::Route::AffinePlusDirectNorms && want_norms)) {
+        const bool seq_update = update && route == star::Route::Seq;
+        const int umax = star::seq_max_updates(Wp, want_norms);
+        for (int u0 = 0; u0 < U; u0 += umax) {
+            const int n = std::min(umax, U - u0);
+            star::SeqArgs a;
+            a.params = params;
+            a.momentum = momentum;
+            a.rows = rows;
+            a.coef = reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
+            a.lr = reinterpret_cast<const float*>(d + lay.lr32) + u0;
+            a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
+            a.U = n;
+            a.mu = (float)plan.mu;
+            a.wd = (float)plan.wd;
+            a.P = P;
+            a.vec_ok = vec_ok ? 1 : 0;
+            a.partials = slot->partials;
+            e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
+            if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");
+            if (want_norms) {
+                e = star::launch_reduce(slot->partials, n, grid, nullptr, norms_out + u0, stream);
+                if (e != hipSuccess) return hip_fail(e, "launch of the norm reduction");
+            }
+        }
+    }
+    STAR_HIP(hipEventRecord(slot->done, stream));
+    return STAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+star_status star_group_update(float* params, float* momentum, const void* const* grad_rows, star_dtype grad_dtype,
+                              int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
+                              float* norms_out, void* hip_stream) {
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, hip_stream);
+}
+
+star_status star_group_norms(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                             const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
+    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, hip_stream);
+}
+
+star_status star_plan_affine(int32_t W, const star_updates* upd, const star_hparams* hp, double M[4], double* B) {
+    g_err.clear();
+    if (!hp || !M || !B) return set_err(STAR_ERR_NULL, "hp, M or B is NULL");
+    star::Plan plan;
+    std::string msg;
+    star_status st = star::build_plan(W, upd, hp, 0, false, &plan, &msg);
+    if (st != STAR_OK) return set_err(st, msg);
+    for (int i = 0; i < 4; ++i) M[i] = plan.M[i];
+    for (int w = 0; w < 2 * W; ++w) B[w] = 0.0;
+    for (int k = 0; k < plan.Wc; ++k) {
+        B[plan.row_of[k]] = plan.B[k];
+        B[W + plan.row_of[k]] = plan.B[plan.Wc + k];
+    }
+    return STAR_OK;
+}
+
+star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hparams* hp, int32_t want_norms,
+                             int32_t* kernel_out, double* fma_seq, double* fma_affine) {
+    g_err.clear();
+    if (!hp) return set_err(STAR_ERR_NULL, "hp is NULL");
+    star::Plan plan;
+    std::string msg;
+    star_status st = star::build_plan(W, upd, hp, 0, want_norms != 0, &plan, &msg);
+    if (st != STAR_OK) return set_err(st, msg);
+    const star::Route r = star::choose_route(plan, 4, true, want_norms != 0, g_kernel_choice);
+    if (kernel_out) *kernel_out = r == star::Route::Seq ? STAR_KERNEL_SEQ : STAR_KERNEL_AFFINE;
+    if (fma_seq) *fma_seq = plan.fma_seq;
+    if (fma_affine) *fma_affine = plan.fma_affine;
+    return STAR_OK;
+}
+
+star_status star_set_kernel(int32_t kernel) {
+    g_err.clear();
+    if (kernel != STAR_KERNEL_AUTO && kernel != STAR_KERNEL_SEQ && kernel != STAR_KERNEL_AFFINE)
+        return set_err(STAR_ERR_KERNEL, "unknown kernel choice");
+    g_kernel_choice = kernel;
+    return STAR_OK;
+}
+
+size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U) {
+    if (P <= 0 || W < 1 || W > STAR_MAX_WORKERS || U <= 0) return 0;
+    const int Wp = star::padded_rows(W);
+    // the grid never exceeds 8 blocks on each of at most 256 compute units
+    const int grid_cap = 256 * star::kMaxBlocksPerCU;
+    return std::max<size_t>(table_layout(U, Wp).total, 64 * 1024) +
+           sizeof(double) * partial_doubles_needed(Wp, U, grid_cap);
+}
+
+const char* star_last_error(void) { return g_err.c_str(); }
+
+const char* star_version(void) { return "libstar 0.1 (gfx950)"; }
+
+void star_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (Slot& s : g_slots)
+        if (s.used || s.done) free_slot(s);
+    g_next_slot = 0;
+}
+
+}  // extern "C"

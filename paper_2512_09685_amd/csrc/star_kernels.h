@@ -1,0 +1,80 @@
+// Launch interface between the C-ABI layer (host) and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+
+#include "star.h"
+
+namespace star {
+
+constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
+constexpr int kMaxBlocksPerCU = 8;   // 32 waves per CU is the hardware ceiling
+
+struct RowPtrs {
+    const void* p[STAR_MAX_WORKERS];
+};
+
+// Coefficients of the collapsed map, passed by value in the kernel arguments
+// so that they live in scalar registers:
+//   p' = p + (dp*p + m01*v + sum_w b0[w] g_w),   v' = m10*p + m11*v + sum_w b1[w] g_w
+struct AffCoef {
+    float dp, m01, m10, m11;
+    float b0[STAR_MAX_WORKERS];
+    float b1[STAR_MAX_WORKERS];
+};
+
+// Row counts the kernels are instantiated for; a plan with Wc rows runs on
+// padded_rows(Wc) >= Wc rows, the extra ones carrying zero coefficients.
+int padded_rows(int Wc);
+
+struct SeqArgs {
+    float* params;
+    float* momentum;
+    RowPtrs rows;
+    const float* coef;     // device [U][Wp]
+    const float* lr;       // device [U]
+    const uint32_t* mask;  // device [U]
+    int32_t U;             // updates in this launch
+    float mu, wd;
+    int64_t P;
+    int32_t vec_ok;        // all buffers 16-byte aligned
+    double* partials;      // device [U][grid] sums of gbar^2 per block (norms only)
+};
+
+// Largest number of updates one launch of the step-by-step kernel accepts
+// (bounded by the LDS tables and, with norms, the per-thread accumulators).
+int seq_max_updates(int Wp, bool norms);
+
+// Step-by-step evaluation.  Returns the grid used in *grid_out (needed to
+// reduce the partials).  grid_cap bounds it.
+hipError_t launch_seq(int Wp, int dtype, bool update, bool norms, const SeqArgs& a, int num_cu, int grid_cap,
+                      int* grid_out, hipStream_t s);
+
+struct AffArgs {
+    float* params;
+    float* momentum;
+    RowPtrs rows;
+    AffCoef cf;
+    int64_t P;
+    int32_t vec_ok;
+    double* partials;  // device [Wp(Wp+1)/2][grid] pairwise-product sums per block (gram only)
+};
+
+// Collapsed evaluation, optionally accumulating the Gram matrix of the rows.
+hipError_t launch_affine(int Wp, int dtype, bool update, bool gram, const AffArgs& a, int num_cu, int grid_cap,
+                         int* grid_out, hipStream_t s);
+
+// out[e] = sum_b partials[e*grid + b] in a fixed order; sums_out (double) and
+// sqrt_out (float, square root of the sum) are each optional.
+hipError_t launch_reduce(const double* partials, int n_out, int grid, double* sums_out, float* sqrt_out,
+                         hipStream_t s);
+
+// norms_out[u] = sqrt( c_u^T Gamma c_u ), Gamma upper-triangular packed [Wp(Wp+1)/2], coef [U][Wp] doubles.
+hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int Wp, float* norms_out,
+                             hipStream_t s);
+
+hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
+
+}  // namespace star

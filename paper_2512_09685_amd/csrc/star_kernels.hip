@@ -1,0 +1,531 @@
+// gfx950 kernels for the group-synchronous parameter update.
+//
+// Layout: every buffer is a flat array of P elements; thread t of the grid
+// owns "chunks" t, t+T, t+2T, ... of VEC consecutive elements (T = threads in
+// the grid), so a wave reads 64 consecutive 16-byte pieces of each row: whole
+// cache lines, every byte used once.  Each gradient row, params and momentum
+// are read once per call; params and momentum are written once.  All state of
+// an element lives in registers between the load and the store.
+//
+// Two evaluations of the U updates of a call (Section 1 items (2), (4);
+// Section 4.2 of the paper define the updates):
+//   seq_kernel  walks the updates one by one with the W gradients of the
+//               element held in registers; group tables sit in LDS.
+//   aff_kernel  applies the U updates as one affine map of (p, v, g_0..g_W-1)
+//               whose coefficients the host composed in double precision.
+// Per-group norms: seq_kernel accumulates gbar_u^2 per thread (LDS slots),
+// aff_kernel accumulates the pairwise products of the rows (Gram matrix);
+// both end with a wave64 DPP reduction and write one partial per block.
+#include <hip/hip_runtime.h>
+
+#include "star_kernels.h"
+
+namespace star {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- row access
+// A "row type" says how VEC consecutive gradient elements are fetched with one
+// load and how element k is widened to fp32.
+struct RowF32 {
+    static constexpr int VEC = 4;
+    typedef f32x4 vec;
+    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
+    }
+    template <int K>
+    static __device__ __forceinline__ float get(const vec& x) { return x[K]; }
+    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
+        return reinterpret_cast<const float*>(row)[j];
+    }
+};
+
+// bf16 is the upper half of an fp32: widening is a shift (even element of a
+// dword) or a mask (odd element); exact, infinities and NaNs carried over.
+template <int K>
+__device__ __forceinline__ float bf16_of(uint32_t dword) {
+    return (K & 1) ? __uint_as_float(dword & 0xffff0000u) : __uint_as_float(dword << 16);
+}
+
+struct RowBf16x8 {
+    static constexpr int VEC = 8;
+    typedef u32x4 vec;
+    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
+    }
+    template <int K>
+    static __device__ __forceinline__ float get(const vec& x) { return bf16_of<K>(x[K >> 1]); }
+    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(row)[j] << 16);
+    }
+};
+
+struct RowBf16x4 {
+    static constexpr int VEC = 4;
+    typedef u32x2 vec;
+    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
+    }
+    template <int K>
+    static __device__ __forceinline__ float get(const vec& x) { return bf16_of<K>(x[K >> 1]); }
+    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
+        return RowBf16x8::load1(row, j);
+    }
+};
+
+// ---------------------------------------------------------------- wave64 sum
+// Sum over the 64 lanes with data-parallel-primitive moves; the total lands in
+// lane 63.  Stages: swap within pairs, within quads, mirror within 8, mirror
+// within 16 (every lane of a 16-lane row now holds the row's sum), then lane 15
+// of rows 0 and 2 is added into rows 1 and 3, and lane 31 into rows 2 and 3.
+// The order of additions is fixed, so the result is reproducible.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_take(float x) {
+    // lanes outside ROW_MASK, or whose source lane is invalid, read 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+
+__device__ __forceinline__ float wave_sum_to_lane63(float x) {
+    x += dpp_take<0xB1, 0xf>(x);   // quad_perm [1,0,3,2]
+    x += dpp_take<0x4E, 0xf>(x);   // quad_perm [2,3,0,1]
+    x += dpp_take<0x141, 0xf>(x);  // row_half_mirror
+    x += dpp_take<0x140, 0xf>(x);  // row_mirror
+    x += dpp_take<0x142, 0xa>(x);  // row_bcast:15 into rows 1, 3
+    x += dpp_take<0x143, 0xc>(x);  // row_bcast:31 into rows 2, 3
+    return x;
+}
+
+// ---------------------------------------------------------------- compile-time loops
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// ================================================================= affine kernel
+template <int W>
+__device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W], const AffCoef& cf) {
+    // increment of p first, one final add: p is perturbed by one rounding of p itself
+    float inc = cf.dp * p;
+    inc = __builtin_fmaf(cf.m01, v, inc);
+    float nv = cf.m10 * p;
+    nv = __builtin_fmaf(cf.m11, v, nv);
+#pragma unroll
+    for (int w = 0; w < W; ++w) {  // ascending worker id
+        inc = __builtin_fmaf(cf.b0[w], g[w], inc);
+        nv = __builtin_fmaf(cf.b1[w], g[w], nv);
+    }
+    p = p + inc;
+    v = nv;
+}
+
+template <int W>
+__device__ __forceinline__ void gram_step(float (&acc)[W * (W + 1) / 2], const float (&g)[W]) {
+    int e = 0;
+#pragma unroll
+    for (int a = 0; a < W; ++a)
+#pragma unroll
+        for (int b = a; b < W; ++b) {
+            acc[e] = __builtin_fmaf(g[a], g[b], acc[e]);
+            ++e;
+        }
+}
+
+template <int W, class R, bool UPDATE, bool GRAM>
+__global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
+                                                     const RowPtrs rows, const AffCoef cf, const int64_t P,
+                                                     const int vec_ok, double* __restrict__ partials) {
+    constexpr int VEC = R::VEC;
+    constexpr int NG = W * (W + 1) / 2;
+    float acc[GRAM ? NG : 1];
+#pragma unroll
+    for (int e = 0; e < (GRAM ? NG : 1); ++e) acc[e] = 0.0f;
+
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const int64_t gtid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nchunk = vec_ok ? P / VEC : 0;
+
+    for (int64_t c = gtid; c < nchunk; c += stride) {
+        typename R::vec g[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) g[w] = R::load(rows.p[w], c);
+        f32x4 pv[VEC / 4], vv[VEC / 4];
+        if constexpr (UPDATE) {
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                pv[q] = reinterpret_cast<const f32x4*>(params)[c * (VEC / 4) + q];
+                vv[q] = reinterpret_cast<const f32x4*>(momentum)[c * (VEC / 4) + q];
+            }
+        }
+        static_for<0, VEC>([&](auto kc) {
+            constexpr int K = decltype(kc)::value;
+            float ge[W];
+            static_for<0, W>([&](auto wc) {
+                constexpr int Wi = decltype(wc)::value;
+                ge[Wi] = R::template get<K>(g[Wi]);
+            });
+            if constexpr (UPDATE) {
+                float pe = pv[K / 4][K % 4], ve = vv[K / 4][K % 4];
+                aff_step<W>(pe, ve, ge, cf);
+                pv[K / 4][K % 4] = pe;
+                vv[K / 4][K % 4] = ve;
+            }
+            if constexpr (GRAM) gram_step<W>(acc, ge);
+        });
+        if constexpr (UPDATE) {
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                reinterpret_cast<f32x4*>(params)[c * (VEC / 4) + q] = pv[q];
+                reinterpret_cast<f32x4*>(momentum)[c * (VEC / 4) + q] = vv[q];
+            }
+        }
+    }
+    // elements not covered by whole chunks (the ragged end, or everything when
+    // some buffer is not 16-byte aligned): same arithmetic, one element at a time
+    for (int64_t j = nchunk * VEC + gtid; j < P; j += stride) {
+        float ge[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) ge[w] = R::load1(rows.p[w], j);
+        if constexpr (UPDATE) {
+            float pe = params[j], ve = momentum[j];
+            aff_step<W>(pe, ve, ge, cf);
+            params[j] = pe;
+            momentum[j] = ve;
+        }
+        if constexpr (GRAM) gram_step<W>(acc, ge);
+    }
+
+    if constexpr (GRAM) {
+        __shared__ float wave_part[kBlock / 64][NG];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int e = 0; e < NG; ++e) {
+            const float s = wave_sum_to_lane63(acc[e]);
+            if (lane == 63) wave_part[wave][e] = s;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < NG; e += kBlock) {
+            double s = 0.0;
+#pragma unroll
+            for (int q = 0; q < kBlock / 64; ++q) s += (double)wave_part[q][e];
+            partials[(int64_t)e * gridDim.x + blockIdx.x] = s;
+        }
+    }
+}
+
+// ================================================================= step-by-step kernel
+// LDS: coef[U][W] | lr[U] | mask[U] | (norms) wave_part[4][U] | nacc[U][kBlock]
+template <int W, bool UPDATE, bool NORMS>
+__device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float (&v)[4],
+                                          const float* s_coef, const float* s_lr, const uint32_t* s_mask,
+                                          float* s_nacc, const int U, const float mu, const float wd) {
+    for (int u = 0; u < U; ++u) {
+        const uint32_t m = __builtin_amdgcn_readfirstlane(s_mask[u]);
+        float gb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int w = 0; w < W; ++w) {  // ascending worker id; the test is uniform over the wave
+            if (m & (1u << w)) {
+                const float c = s_coef[u * W + w];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) gb[k] = __builtin_fmaf(c, g[w][k], gb[k]);
+            }
+        }
+        if constexpr (NORMS) {
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s = __builtin_fmaf(gb[k], gb[k], s);  // unused slots hold 0
+            s_nacc[u * kBlock + threadIdx.x] += s;
+        }
+        if constexpr (UPDATE) {
+            const float lr = s_lr[u];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float d = __builtin_fmaf(wd, p[k], gb[k]);   // d = gbar + wd p
+                v[k] = __builtin_fmaf(mu, v[k], d);                // v = mu v + d
+                p[k] = __builtin_fmaf(-lr, v[k], p[k]);            // p = p - lr v
+            }
+        }
+    }
+}
+
+template <int W, class R, bool UPDATE, bool NORMS>
+__global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params, float* __restrict__ momentum,
+                                                     const RowPtrs rows, const float* __restrict__ t_coef,
+                                                     const float* __restrict__ t_lr,
+                                                     const uint32_t* __restrict__ t_mask, const int U,
+                                                     const float mu, const float wd, const int64_t P,
+                                                     const int vec_ok, double* __restrict__ partials) {
+    static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
+    extern __shared__ float lds[];
+    float* s_coef = lds;
+    float* s_lr = s_coef + U * W;
+    uint32_t* s_mask = reinterpret_cast<uint32_t*>(s_lr + U);
+    float* s_wave = reinterpret_cast<float*>(s_mask + U);
+    float* s_nacc = s_wave + (NORMS ? (kBlock / 64) * U : 0);
+    for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
+    for (int i = threadIdx.x; i < U; i += kBlock) {
+        s_lr[i] = t_lr[i];
+        s_mask[i] = t_mask[i];
+    }
+    if constexpr (NORMS)
+        for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
+    __syncthreads();
+
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const int64_t gtid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nchunk = vec_ok ? P / 4 : 0;
+
+    for (int64_t c = gtid; c < nchunk; c += stride) {
+        typename R::vec raw[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) raw[w] = R::load(rows.p[w], c);
+        float p[4] = {0, 0, 0, 0}, v[4] = {0, 0, 0, 0};
+        if constexpr (UPDATE) {
+            const f32x4 pv = reinterpret_cast<const f32x4*>(params)[c];
+            const f32x4 vv = reinterpret_cast<const f32x4*>(momentum)[c];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                p[k] = pv[k];
+                v[k] = vv[k];
+            }
+        }
+        float g[W][4];
+        static_for<0, W>([&](auto wc) {
+            constexpr int Wi = decltype(wc)::value;
+            static_for<0, 4>([&](auto kc) {
+                constexpr int K = decltype(kc)::value;
+                g[Wi][K] = R::template get<K>(raw[Wi]);
+            });
+        });
+        seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        if constexpr (UPDATE) {
+            f32x4 pv, vv;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                pv[k] = p[k];
+                vv[k] = v[k];
+            }
+            reinterpret_cast<f32x4*>(params)[c] = pv;
+            reinterpret_cast<f32x4*>(momentum)[c] = vv;
+        }
+    }
+    for (int64_t j = nchunk * 4 + gtid; j < P; j += stride) {
+        float g[W][4];
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            g[w][0] = R::load1(rows.p[w], j);
+            g[w][1] = g[w][2] = g[w][3] = 0.0f;
+        }
+        float p[4] = {0, 0, 0, 0}, v[4] = {0, 0, 0, 0};
+        if constexpr (UPDATE) {
+            p[0] = params[j];
+            v[0] = momentum[j];
+        }
+        seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        if constexpr (UPDATE) {
+            params[j] = p[0];
+            momentum[j] = v[0];
+        }
+    }
+
+    if constexpr (NORMS) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        for (int u = 0; u < U; ++u) {
+            const float s = wave_sum_to_lane63(s_nacc[u * kBlock + threadIdx.x]);
+            if (lane == 63) s_wave[wave * U + u] = s;
+        }
+        __syncthreads();
+        for (int u = threadIdx.x; u < U; u += kBlock) {
+            double s = 0.0;
+#pragma unroll
+            for (int q = 0; q < kBlock / 64; ++q) s += (double)s_wave[q * U + u];
+            partials[(int64_t)u * gridDim.x + blockIdx.x] = s;
+        }
+    }
+}
+
+// ================================================================= finishing kernels
+__global__ __launch_bounds__(kBlock) void reduce_kernel(const double* __restrict__ partials, const int grid,
+                                                        double* __restrict__ sums_out,
+                                                        float* __restrict__ sqrt_out) {
+    __shared__ double s_part[kBlock];
+    const int e = blockIdx.x;
+    double s = 0.0;
+    for (int b = threadIdx.x; b < grid; b += kBlock) s += partials[(int64_t)e * grid + b];
+    s_part[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (sums_out) sums_out[e] = s_part[0];
+        if (sqrt_out) sqrt_out[e] = (float)sqrt(s_part[0]);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __restrict__ gamma,
+                                                            const double* __restrict__ coef, const int U,
+                                                            const int W, float* __restrict__ norms_out) {
+    const int u = blockIdx.x * kBlock + threadIdx.x;
+    if (u >= U) return;
+    const double* c = coef + (int64_t)u * W;
+    double s = 0.0;
+    int e = 0;
+    for (int a = 0; a < W; ++a)
+        for (int b = a; b < W; ++b, ++e) {
+            const double t = c[a] * c[b] * gamma[e];
+            s += (a == b) ? t : 2.0 * t;
+        }
+    norms_out[u] = (float)sqrt(s > 0.0 ? s : 0.0);
+}
+
+__global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, const int64_t n, const float value) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+// ================================================================= launchers
+int padded_rows(int Wc) {
+    if (Wc <= 16) return Wc < 1 ? 1 : Wc;
+    return (Wc + 3) / 4 * 4;
+}
+
+namespace {
+
+int resident_blocks(const void* kernel, size_t lds_bytes) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, lds_bytes) != hipSuccess || n < 1) n = 1;
+    return n > kMaxBlocksPerCU ? kMaxBlocksPerCU : n;
+}
+
+int pick_grid(int64_t P, int elems_per_thread, int num_cu, int blocks_per_cu, int grid_cap) {
+    const int64_t per_block = (int64_t)kBlock * elems_per_thread;
+    int64_t need = (P + per_block - 1) / per_block;
+    int64_t g = (int64_t)num_cu * blocks_per_cu;
+    if (g > grid_cap) g = grid_cap;
+    if (need < g) g = need;
+    return g < 1 ? 1 : (int)g;
+}
+
+size_t seq_lds_bytes(int W, int U, bool norms) {
+    return sizeof(float) * ((size_t)U * W + 2 * (size_t)U + (norms ? (size_t)(kBlock / 64) * U + (size_t)U * kBlock : 0));
+}
+
+template <int W, class R, bool UPDATE, bool NORMS>
+hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
+    auto kern = seq_kernel<W, R, UPDATE, NORMS>;
+    const size_t lds = seq_lds_bytes(W, a.U, NORMS);
+    const int grid = pick_grid(a.P, 4, num_cu, resident_blocks(reinterpret_cast<const void*>(kern), lds), grid_cap);
+    *grid_out = grid;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
+                       a.U, a.mu, a.wd, a.P, a.vec_ok, a.partials);
+    return hipGetLastError();
+}
+
+template <int W, class R, bool UPDATE, bool GRAM>
+hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
+    auto kern = aff_kernel<W, R, UPDATE, GRAM>;
+    static const int blocks_per_cu = resident_blocks(reinterpret_cast<const void*>(kern), 0);
+    const int grid = pick_grid(a.P, R::VEC, num_cu, blocks_per_cu, grid_cap);
+    *grid_out = grid;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
+                       a.partials);
+    return hipGetLastError();
+}
+
+template <int W>
+hipError_t launch_seq_w(int dtype, bool update, bool norms, const SeqArgs& a, int num_cu, int grid_cap,
+                        int* grid_out, hipStream_t s) {
+    if (dtype == STAR_F32) {
+        if (update && norms) return launch_seq_t<W, RowF32, true, true>(a, num_cu, grid_cap, grid_out, s);
+        if (update) return launch_seq_t<W, RowF32, true, false>(a, num_cu, grid_cap, grid_out, s);
+        return launch_seq_t<W, RowF32, false, true>(a, num_cu, grid_cap, grid_out, s);
+    }
+    if (update && norms) return launch_seq_t<W, RowBf16x4, true, true>(a, num_cu, grid_cap, grid_out, s);
+    if (update) return launch_seq_t<W, RowBf16x4, true, false>(a, num_cu, grid_cap, grid_out, s);
+    return launch_seq_t<W, RowBf16x4, false, true>(a, num_cu, grid_cap, grid_out, s);
+}
+
+template <int W>
+hipError_t launch_aff_w(int dtype, bool update, bool gram, const AffArgs& a, int num_cu, int grid_cap,
+                        int* grid_out, hipStream_t s) {
+    if constexpr (W <= 16) {
+        if (gram) {
+            // with the W(W+1)/2 accumulators live, 4 elements per thread keep the kernel at two waves per SIMD
+            if (dtype == STAR_F32) {
+                if (update) return launch_aff_t<W, RowF32, true, true>(a, num_cu, grid_cap, grid_out, s);
+                return launch_aff_t<W, RowF32, false, true>(a, num_cu, grid_cap, grid_out, s);
+            }
+            if (update) return launch_aff_t<W, RowBf16x4, true, true>(a, num_cu, grid_cap, grid_out, s);
+            return launch_aff_t<W, RowBf16x4, false, true>(a, num_cu, grid_cap, grid_out, s);
+        }
+    }
+    if (gram || !update) return hipErrorInvalidValue;
+    if (dtype == STAR_F32) return launch_aff_t<W, RowF32, true, false>(a, num_cu, grid_cap, grid_out, s);
+    return launch_aff_t<W, RowBf16x8, true, false>(a, num_cu, grid_cap, grid_out, s);
+}
+
+}  // namespace
+
+int seq_max_updates(int Wp, bool norms) {
+    // stay inside 64 KB of LDS per workgroup
+    const size_t budget = 60 * 1024;
+    int u = 1;
+    while (u < 256 && seq_lds_bytes(Wp, u + 1, norms) <= budget) ++u;
+    return u;
+}
+
+#define STAR_FOR_EACH_W(X)                                                                                    \
+    X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(20) X(24) X(28) \
+    X(32)
+
+hipError_t launch_seq(int Wp, int dtype, bool update, bool norms, const SeqArgs& a, int num_cu, int grid_cap,
+                      int* grid_out, hipStream_t s) {
+    if (!update && !norms) return hipErrorInvalidValue;
+    if (a.U < 1 || a.U > seq_max_updates(Wp, norms)) return hipErrorInvalidValue;
+    switch (Wp) {
+#define X(N) case N: return launch_seq_w<N>(dtype, update, norms, a, num_cu, grid_cap, grid_out, s);
+        STAR_FOR_EACH_W(X)
+#undef X
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_affine(int Wp, int dtype, bool update, bool gram, const AffArgs& a, int num_cu, int grid_cap,
+                         int* grid_out, hipStream_t s) {
+    if (!update && !gram) return hipErrorInvalidValue;
+    switch (Wp) {
+#define X(N) case N: return launch_aff_w<N>(dtype, update, gram, a, num_cu, grid_cap, grid_out, s);
+        STAR_FOR_EACH_W(X)
+#undef X
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_reduce(const double* partials, int n_out, int grid, double* sums_out, float* sqrt_out,
+                         hipStream_t s) {
+    if (n_out < 1) return hipSuccess;
+    hipLaunchKernelGGL(reduce_kernel, dim3(n_out), dim3(kBlock), 0, s, partials, grid, sums_out, sqrt_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int Wp, float* norms_out,
+                             hipStream_t s) {
+    if (U < 1) return hipSuccess;
+    hipLaunchKernelGGL(gram_norms_kernel, dim3((U + kBlock - 1) / kBlock), dim3(kBlock), 0, s, gamma, coef, U, Wp,
+                       norms_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s) {
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, dst, n, value);
+    return hipGetLastError();
+}
+
+}  // namespace star

@@ -1,0 +1,268 @@
+"""GPU parity: libstar (through its C ABI) against the CPU oracle, element by
+element, on seeded inputs small enough for the oracle yet spanning many
+workgroups, several chunks per thread and a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_09685_amd as star
+import workloads
+from oracle import star_oracle as so
+from gpu_util import TOL, gpu_update, rand_rows, rand_stream, to_dev_rows
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = {"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE}
+
+
+def check(p, v, n, ep, ev, en, dtype, what=""):
+    tol = TOL[dtype]
+    e_p, e_v = so.max_rel_err(p, ep), so.max_rel_err(v, ev)
+    print(f"[{what}] err p={e_p:.3g} v={e_v:.3g}", end="")
+    assert e_p <= tol and e_v <= tol, (what, e_p, e_v)
+    if en is not None:
+        e_n = float(np.max(np.abs(n - en) / np.maximum(np.abs(en), 1e-30))) if len(en) else 0.0
+        print(f" norms={e_n:.3g}", end="")
+        assert e_n <= tol, (what, e_n)
+    print(flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kname", ["seq", "affine", "auto"])
+@pytest.mark.parametrize("W,P,U,norms", [
+    (1, 1, 1, True), (2, 3, 2, False), (4, 5, 10, True), (3, 1023, 7, True), (5, 1025, 12, False),
+    (8, 4099, 24, True), (16, 70001, 16, True), (17, 33333, 9, True), (32, 50000, 12, False),
+    (32, 20003, 6, True), (12, 600011, 20, True),
+])
+def test_random_shapes(dtype, kname, W, P, U, norms):
+    rng = np.random.default_rng(1000 * W + U + (7 if dtype == "bf16" else 0))
+    rows = rand_rows(rng, W, P, dtype)
+    offs, mem, st = rand_stream(rng, W, U, stale=4)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+    print(f"case W={W} P={P} U={U} norms={norms} {dtype} {kname}", flush=True)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, staleness=st, want_norms=norms, **hp)
+    p, v, n = gpu_update(p0, v0, rows, offs, mem, staleness=st, want_norms=norms, kernel=KERNELS[kname], **hp)
+    check(p, v, n, ep, ev, en, dtype, f"{kname} W={W} P={P} U={U}")
+
+
+@pytest.mark.parametrize("name", workloads.ORDER)
+@pytest.mark.parametrize("kname", ["seq", "auto"])
+def test_workload_structure_scaled_down(name, kname):
+    """Each of the five workloads with its own W, dtype, group mix, weights and
+    hyper-parameters, at a shard length the oracle finishes in seconds."""
+    wl = workloads.WORKLOADS[name].scaled(262144 + 4 * 257 + 3)
+    p0 = workloads.make_params(wl, 0).numpy()
+    p, v = p0.copy(), np.zeros_like(p0)
+    ep, ev = p0.copy(), np.zeros_like(p0)
+    print(f"workload {name} {kname}", flush=True)
+    rows = None
+    for call in range(wl.calls):
+        if rows is None or wl.fresh_grads_per_call:
+            rows = workloads.rows_to_numpy(workloads.make_grad_rows(wl, 0, call))
+        s = workloads.make_update_stream(wl, 0, call)
+        hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+        ep, ev, en = so.group_update(ep, ev, rows, s["offsets"], s["members"], staleness=s["staleness"],
+                                     want_norms=wl.norms, **hp)
+        p, v, n = gpu_update(p, v, rows, s["offsets"], s["members"], staleness=s["staleness"], want_norms=wl.norms,
+                             kernel=KERNELS[kname], **hp)
+        check(p, v, n, ep, ev, en, wl.grad_dtype, f"{name} call {call} {kname}")
+
+
+def test_member_order_is_bitwise_irrelevant():
+    rng = np.random.default_rng(5)
+    W, P, U = 9, 10007, 11
+    rows = rand_rows(rng, W, P, "f32")
+    offs, mem, st = rand_stream(rng, W, U, stale=3)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = rng.standard_normal(P).astype(np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale", want_norms=True)
+    mem2, st2 = mem.copy(), st.copy()
+    for u in range(U):
+        perm = rng.permutation(offs[u + 1] - offs[u]) + offs[u]
+        mem2[offs[u]:offs[u + 1]], st2[offs[u]:offs[u + 1]] = mem[perm], st[perm]
+    for k in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        a = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
+        b = gpu_update(p0, v0, rows, offs, mem2, staleness=st2, kernel=k, **hp)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+
+
+def test_run_to_run_bitwise_reproducible():
+    rng = np.random.default_rng(6)
+    W, P, U = 16, 300001, 20
+    rows = rand_rows(rng, W, P, "bf16")
+    offs, mem, st = rand_stream(rng, W, U, stale=3)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale", want_norms=True)
+    for k in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        a = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
+        b = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+
+
+def test_batch_split_carries_state():
+    """One call with U updates against two calls with U1 + U2: the step-by-step
+    kernel rounds after every update either way, so it must agree bit for bit;
+    the collapsed kernel agrees to rounding."""
+    rng = np.random.default_rng(7)
+    W, P, U, k = 6, 50001, 14, 5
+    rows = rand_rows(rng, W, P, "f32")
+    offs, mem, _ = rand_stream(rng, W, U)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = rng.standard_normal(P).astype(np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, want_norms=True)
+    for kern, exact in ((star.KERNEL_SEQ, True), (star.KERNEL_AFFINE, False)):
+        p, v, n = gpu_update(p0, v0, rows, offs, mem, kernel=kern, **hp)
+        pa, va, na = gpu_update(p0, v0, rows, offs[:k + 1], mem[:offs[k]], kernel=kern, **hp)
+        pb, vb, nb = gpu_update(pa, va, rows, offs[k:] - offs[k], mem[offs[k]:], kernel=kern, **hp)
+        if exact:
+            assert np.array_equal(p, pb) and np.array_equal(v, vb)
+            assert np.array_equal(n, np.concatenate([na, nb]))
+        else:
+            assert so.max_rel_err(pb, p) < 1e-6 and so.max_rel_err(vb, v) < 1e-6
+            np.testing.assert_allclose(np.concatenate([na, nb]), n, rtol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unaligned_buffers_give_identical_results(dtype):
+    rng = np.random.default_rng(8)
+    W, P, U = 5, 40009, 8
+    rows = rand_rows(rng, W, P + 3, dtype)
+    offs, mem, _ = rand_stream(rng, W, U)
+    p0 = rng.standard_normal(P + 3).astype(np.float32)
+    v0 = rng.standard_normal(P + 3).astype(np.float32)
+    us = star.UpdateStream(offs, mem)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3)
+    for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        star.star_set_kernel(kern)
+        outs = []
+        for shift in (0, 1):          # shift 1: every base pointer is off the 16-byte grid
+            drows = [r[shift:shift + P].clone() if shift == 0 else r[shift:shift + P] for r in to_dev_rows(rows)]
+            rows_same = [r[0:P] for r in rows] if shift == 0 else [r[1:1 + P] for r in rows]
+            p = torch.from_numpy(p0).cuda()[shift:shift + P]
+            v = torch.from_numpy(v0).cuda()[shift:shift + P]
+            if shift == 0:
+                p, v = p.clone(), v.clone()
+            n = torch.zeros(U, device="cuda")
+            star.star_group_update(p, v, drows, us, norms_out=n, **hp)
+            torch.cuda.synchronize()
+            ep, ev, en = so.group_update(p0[shift:shift + P], v0[shift:shift + P], rows_same, offs, mem,
+                                         want_norms=True, **hp)
+            check(p.cpu().numpy(), v.cpu().numpy(), n.cpu().numpy(), ep, ev, en, dtype, f"shift {shift}")
+        star.star_set_kernel(star.KERNEL_AUTO)
+
+
+def test_norms_entry_point_matches_update_norms():
+    rng = np.random.default_rng(9)
+    for W, P, U, dtype in ((7, 123457, 10, "f32"), (16, 90001, 30, "bf16"), (24, 30011, 8, "f32")):
+        rows = rand_rows(rng, W, P, dtype)
+        offs, mem, st = rand_stream(rng, W, U, stale=5)
+        en = so.group_norms(rows, offs, mem, wmode="stale", staleness=st)
+        drows = to_dev_rows(rows)
+        us = star.UpdateStream(offs, mem, st)
+        for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AUTO):
+            star.star_set_kernel(kern)
+            n = torch.full((U,), -1.0, device="cuda")
+            star.star_group_norms(drows, us, n, wmode="stale")
+            torch.cuda.synchronize()
+            star.star_set_kernel(star.KERNEL_AUTO)
+            err = np.max(np.abs(n.cpu().numpy() - en) / en)
+            print(f"norms-only W={W} kern={kern} err={err:.3g}", flush=True)
+            assert err <= TOL[dtype]
+
+
+def test_long_stream_is_chunked():
+    """More updates than one launch of the step-by-step kernel holds."""
+    rng = np.random.default_rng(10)
+    W, P, U = 4, 9001, 300
+    rows = rand_rows(rng, W, P, "f32", std=1e-3)
+    offs, mem, _ = rand_stream(rng, W, U)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=0.01, momentum_coef=0.9, weight_decay=1e-4, want_norms=True)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, **hp)
+    for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        p, v, n = gpu_update(p0, v0, rows, offs, mem, kernel=kern, **hp)
+        tol = 4e-6 if kern == star.KERNEL_SEQ else 1e-6      # 300 roundings of the state in the literal form
+        assert so.max_rel_err(p, ep) <= tol and so.max_rel_err(v, ev) <= tol
+        np.testing.assert_allclose(n, en, rtol=1e-6)
+
+
+def test_special_modes_explicit_coefficients_scaled_lr_per_update_lr():
+    rng = np.random.default_rng(11)
+    W, P, U = 8, 20001, 9
+    rows = rand_rows(rng, W, P, "f32")
+    offs, mem, _ = rand_stream(rng, W, U)
+    cf = rng.uniform(-1, 1, len(mem)).astype(np.float32)
+    lrs = rng.uniform(0.01, 0.1, U).astype(np.float32)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = rng.standard_normal(P).astype(np.float32)
+    hp = dict(lr=0.3, momentum_coef=0.8, weight_decay=1e-2, wmode="explicit", scale_lr_by_group=True, want_norms=True)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, coeff=cf, lr_per_update=lrs, **hp)
+    for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        p, v, n = gpu_update(p0, v0, rows, offs, mem, coeff=cf, lr_per_update=lrs, kernel=kern, **hp)
+        check(p, v, n, ep, ev, en, "f32", f"explicit kern={kern}")
+
+
+def test_unreferenced_rows_may_be_null():
+    rng = np.random.default_rng(12)
+    W, P = 6, 5003
+    rows = rand_rows(rng, W, P, "f32")
+    offs, mem = np.array([0, 2, 3], np.int32), np.array([4, 1, 4], np.int32)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=0.1, momentum_coef=0.9, weight_decay=0.0, want_norms=True)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, **hp)
+    sparse = [r if w in (1, 4) else None for w, r in enumerate(rows)]
+    for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        p, v, n = gpu_update(p0, v0, sparse, offs, mem, kernel=kern, **hp)
+        check(p, v, n, ep, ev, en, "f32", f"null rows kern={kern}")
+
+
+def test_empty_cases_on_device():
+    p = torch.ones(16, device="cuda")
+    v = torch.ones(16, device="cuda")
+    rows = [torch.ones(16, device="cuda")]
+    star.star_group_update(p, v, rows, star.UpdateStream([0], []), lr=0.1, momentum_coef=0.9)
+    torch.cuda.synchronize()
+    assert torch.all(p == 1) and torch.all(v == 1)
+    n = torch.full((2,), 5.0, device="cuda")
+    e = torch.empty(0, device="cuda")
+    star.star_group_update(e, e, [e], star.UpdateStream([0, 1, 2], [0, 0]), lr=0.1, momentum_coef=0.9, norms_out=n)
+    torch.cuda.synchronize()
+    assert n.tolist() == [0.0, 0.0]
+
+
+def test_non_default_stream_and_back_to_back_calls():
+    """Four calls enqueued without a host sync on a side stream, state carried
+    from call to call (how a streamed batch of updates arrives)."""
+    rng = np.random.default_rng(13)
+    W, P, U = 16, 100003, 16
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    ep, ev = p0.copy(), np.zeros(P, np.float32)
+    s = torch.cuda.Stream()
+    p = torch.from_numpy(p0).cuda()
+    v = torch.zeros(P, device="cuda")
+    sets, streams, norms = [], [], []
+    for call in range(4):
+        rows = rand_rows(rng, W, P, "bf16", std=5e-4)
+        offs, mem, st = rand_stream(rng, W, U, min_y=2, stale=8)
+        sets.append((rows, to_dev_rows(rows)))
+        streams.append((offs, mem, st))
+        norms.append(torch.zeros(U, device="cuda"))
+    torch.cuda.synchronize()
+    hp = dict(lr=0.01, momentum_coef=0.9, weight_decay=1e-4, wmode="stale")
+    for call in range(4):
+        offs, mem, st = streams[call]
+        star.star_group_update(p, v, sets[call][1], star.UpdateStream(offs, mem, st), norms_out=norms[call],
+                               stream=s, **hp)
+    s.synchronize()
+    for call in range(4):
+        offs, mem, st = streams[call]
+        ep, ev, en = so.group_update(ep, ev, sets[call][0], offs, mem, staleness=st, want_norms=True, **hp)
+        np.testing.assert_allclose(norms[call].cpu().numpy(), en, rtol=TOL["bf16"])
+    check(p.cpu().numpy(), v.cpu().numpy(), None, ep, ev, None, "bf16", "4 streamed calls")

@@ -1,0 +1,132 @@
+"""Host-side logic of libstar, exercised without a GPU: the library loads, it
+exports what include/star.h declares, argument checks return their status
+codes before any device work, and the collapsed affine map agrees with the
+step-by-step oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2512_09685_amd as star
+from paper_2512_09685_amd import binding
+from oracle import star_oracle as so
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "star.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
+    assert {"star_group_update", "star_group_norms", "star_plan_affine", "star_plan_choice", "star_set_kernel",
+            "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
+    lib = star.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in star.star_version()
+
+
+def _call_update(W=4, P=8, offsets=(0, 2), members=(0, 1), staleness=None, coeff=None, lr_arr=None, lr=0.1, mu=0.9,
+                 wd=0.0, wmode=0, dtype=0, params=0x1000, momentum=0x2000, rows="fake", upd_null=False, hp_null=False):
+    """Calls star_group_update with fake (never dereferenced) device addresses:
+    every case here must be rejected before the device is touched."""
+    lib = star.load_library()
+    us = star.UpdateStream(offsets, members, staleness, coeff, lr_arr)
+    hp = binding._HParams(lr, mu, wd, wmode, 0)
+    ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
+    return lib.star_group_update(params, momentum, None if rows is None else ptrs, dtype, P, W,
+                                 None if upd_null else ctypes.byref(us.c), None if hp_null else ctypes.byref(hp),
+                                 None, None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(upd_null=True), 1), (dict(hp_null=True), 1), (dict(rows=None), 1), (dict(params=None), 1),
+    (dict(P=-1), 2), (dict(W=0), 2), (dict(W=33), 2),
+    (dict(dtype=7), 5),
+    (dict(offsets=(0, 0)), 3), (dict(offsets=(0, 2), members=(1, 1)), 3), (dict(members=(0, 4)), 3),
+    (dict(members=(-1, 0)), 3), (dict(offsets=(1, 2)), 3), (dict(offsets=(0, 2, 1), members=(0, 1)), 3),
+    (dict(lr=float("nan")), 4), (dict(mu=float("inf")), 4), (dict(wd=float("nan")), 4), (dict(wmode=9), 4),
+    (dict(wmode=1, staleness=(0, -1)), 4), (dict(wmode=2, coeff=(1.0, float("inf"))), 4),
+    (dict(wmode=2), 1), (dict(lr_arr=(float("nan"),)), 4),
+])
+def test_argument_checks(kw, status):
+    assert _call_update(**kw) == status
+    assert star.last_error() != ""
+
+
+def test_empty_stream_and_empty_shard_are_no_ops():
+    assert _call_update(offsets=(0,), members=()) == 0          # U = 0
+    assert _call_update(P=0) == 0                                # P = 0, no norms
+    assert star.last_error() == ""
+
+
+def test_set_kernel_validation():
+    lib = star.load_library()
+    assert lib.star_set_kernel(5) == 6
+    assert lib.star_set_kernel(0) == 0
+
+
+def _rand_stream(rng, W, U, stale=None):
+    offs, mem = [0], []
+    for _ in range(U):
+        y = int(rng.integers(1, W + 1))
+        mem += [int(x) for x in rng.permutation(W)[:y]]
+        offs.append(len(mem))
+    st = None if stale is None else rng.integers(0, stale + 1, size=len(mem)).astype(np.int32)
+    return np.array(offs, np.int32), np.array(mem, np.int32), st
+
+
+@pytest.mark.parametrize("seed,W,U,wd,scale", [(0, 5, 9, 0.0, False), (1, 16, 64, 1e-2, False), (2, 8, 33, 0.1, True),
+                                               (3, 32, 128, 1e-4, False)])
+def test_affine_map_equals_sequential_oracle(seed, W, U, wd, scale):
+    rng = np.random.default_rng(seed)
+    P = 50
+    rows = [rng.standard_normal(P).astype(np.float32) for _ in range(W)]
+    offs, mem, st = _rand_stream(rng, W, U, stale=4)
+    lrs = rng.uniform(0.01, 0.2, U).astype(np.float32)
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = rng.standard_normal(P).astype(np.float32)
+    us = star.UpdateStream(offs, mem, st, None, lrs)
+    M, B = star.star_plan_affine(W, us, lr=0.0, momentum_coef=0.9, weight_decay=wd, wmode="stale",
+                                 scale_lr_by_group=scale)
+    p, v, _ = so.group_update(p0, v0, rows, offs, mem, lr=0.0, momentum_coef=0.9, weight_decay=wd, wmode="stale",
+                              staleness=st, lr_per_update=lrs, scale_lr_by_group=scale, mode="f64")
+    G = np.stack(rows).astype(np.float64)
+    x0 = np.stack([p0, v0]).astype(np.float64)
+    x = M @ x0 + B @ G
+    np.testing.assert_allclose(x[0], p, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(x[1], v, rtol=0, atol=1e-12)
+
+
+def test_affine_hand_case():
+    # lr 0.5, mu 0.5, no decay, groups {0,1} then {1}:  p_2 = p_0 - 0.75*gbar_0 - 0.5*gbar_1 ... in worker terms
+    us = star.UpdateStream([0, 2, 3], [0, 1, 1])
+    M, B = star.star_plan_affine(2, us, lr=0.5, momentum_coef=0.5)
+    # u0: v=gbar0, p=p-0.5 gbar0 ; u1: v=0.5 gbar0 + g1, p = p - 0.5 gbar0 - 0.25 gbar0 - 0.5 g1
+    # gbar0 = (g0+g1)/2  ->  p: g0 coef -0.375, g1 coef -0.375-0.5 ; v: g0 0.25, g1 1.25
+    np.testing.assert_allclose(M, [[1.0, -0.5 * 0.5 - 0.5 * 0.25], [0.0, 0.25]], atol=1e-15)
+    np.testing.assert_allclose(B, [[-0.375, -0.875], [0.25, 1.25]], atol=1e-15)
+
+
+def test_unused_rows_get_zero_coefficients():
+    us = star.UpdateStream([0, 1, 3], [2, 0, 2])
+    M, B = star.star_plan_affine(4, us, lr=0.1, momentum_coef=0.9)
+    assert np.all(B[:, 1] == 0) and np.all(B[:, 3] == 0) and np.all(B[:, 0] != 0) and np.all(B[:, 2] != 0)
+
+
+def test_cost_model_prefers_literal_steps_for_one_update_and_collapse_for_many():
+    one = star.UpdateStream([0, 4], [0, 1, 2, 3])
+    k, fs, fa = star.star_plan_choice(4, one, lr=0.1, momentum_coef=0.9)
+    assert (k, fs, fa) == (star.KERNEL_SEQ, 7.0, 12.0)
+    rng = np.random.default_rng(0)
+    offs, mem, _ = _rand_stream(rng, 16, 64)
+    many = star.UpdateStream(offs, mem)
+    k, fs, fa = star.star_plan_choice(16, many, lr=0.1, momentum_coef=0.9, want_norms=True)
+    assert k == star.KERNEL_AFFINE and fa == 36 + 136 and fs == len(mem) + 4 * 64
+
+
+def test_workspace_bytes_is_modest():
+    assert star.star_workspace_bytes(0, 4, 4) == 0
+    assert 0 < star.star_workspace_bytes(340_000_000, 16, 64) < 8 << 20
