@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the group-synchronous parameter update on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: all
+calls of the workload (one star_group_update with U updates; four back-to-back
+calls for the streamed BERT-large workload), gradient norms included where the
+workload asks for them.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_base",
+                    help="headline workload: tiny | resnet50 | bert_base | vgg16 | bert_large")
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per-config table)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine"])
+    return ap.parse_args()
+
+
+def kernel_label(star, wl, us):
+    k, fs, fa = star.star_plan_choice(wl.W, us, lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay,
+                                      wmode=wl.wmode, want_norms=wl.norms)
+    dt = "RowF32" if wl.grad_dtype == "f32" else ("RowBf16x4" if wl.norms and wl.W <= 16 else "RowBf16x8")
+    if k == star.KERNEL_AFFINE:
+        return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
+    return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa
+
+
+def measure(wl, steps, warmup, torch, star, workloads):
+    """Times `steps` steps of workload `wl`; returns a dict of results."""
+    dev = "cuda"
+    stream = torch.cuda.Stream()
+    p = workloads.make_params(wl, 0, dev)
+    v = workloads.make_momentum(wl, dev)
+    nsets = wl.calls if wl.fresh_grads_per_call else 1
+    sets = [workloads.make_grad_rows(wl, 0, c, dev) for c in range(nsets)]
+    streams = []
+    for c in range(wl.calls):
+        s = workloads.make_update_stream(wl, 0, c)
+        streams.append(star.UpdateStream(s["offsets"], s["members"], s["staleness"]))
+    norms = [torch.zeros(wl.U, device=dev) for _ in range(wl.calls)] if wl.norms else [None] * wl.calls
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    torch.cuda.synchronize()
+
+    def step():
+        for c in range(wl.calls):
+            star.star_group_update(p, v, sets[c % nsets], streams[c], norms_out=norms[c], stream=stream, **hp)
+
+    for _ in range(warmup):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        step()
+    e1.record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = ev_ms / steps
+    assert bool(torch.isfinite(p[:: max(1, wl.P // 4096)]).all()), "non-finite parameters after the timed steps"
+
+    used = set()
+    for us in streams:
+        used |= set(int(x) for x in us.members)
+    bytes_per_call = wl.algorithmic_bytes_per_call(len(used))
+    bytes_per_step = bytes_per_call * wl.calls
+    gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    label, fs, fa = kernel_label(star, wl, streams[0])
+    res = {
+        "workload": wl.name, "P": wl.P, "W": wl.W, "U_per_call": wl.U, "calls_per_step": wl.calls,
+        "grad_dtype": wl.grad_dtype, "norms": wl.norms,
+        "group_updates_per_s": wl.U * wl.calls / (ms_per_step * 1e-3),
+        "ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms / steps,
+        "algorithmic_bytes_per_step": bytes_per_step, "bytes_per_element": bytes_per_call / wl.P,
+        "hbm_gbps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "kernel": label,
+        "fma_per_element_seq": fs, "fma_per_element_affine": fa,
+        "launch_ms": ms_per_step / wl.calls, "bytes_per_launch": bytes_per_call,
+    }
+    del p, v, sets, norms
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(wl, torch, workloads):
+    """The CPU oracle (exact fp64 mode, one thread) on a contiguous slice of the
+    same workload, sized for roughly 15 s; elements are independent, so the
+    full-shard rate is the slice's rate scaled by the slice fraction."""
+    import numpy as np
+    from oracle import star_oracle as so
+
+    def run(P):
+        w = wl.scaled(P)
+        rows = workloads.rows_to_numpy(workloads.make_grad_rows(w, 0, 0, "cpu"))
+        p0 = workloads.make_params(w, 0, "cpu").numpy()
+        s = workloads.make_update_stream(w, 0, 0)
+        t = time.perf_counter()
+        so.group_update(p0, np.zeros_like(p0), rows, s["offsets"], s["members"], staleness=s["staleness"],
+                        lr=w.lr, momentum_coef=w.momentum, weight_decay=w.weight_decay, wmode=w.wmode,
+                        want_norms=w.norms, mode="exact")
+        return time.perf_counter() - t
+
+    try:
+        os.sched_setaffinity(0, {sorted(os.sched_getaffinity(0))[0]})
+    except (AttributeError, OSError):
+        pass
+    probe_P = 20000
+    t_probe = max(run(probe_P), 1e-4)
+    P = int(min(wl.P, max(probe_P, probe_P * 15.0 / t_probe)))
+    t = run(P)
+    full_call_s = t * wl.P / P
+    return {
+        "value": wl.U / full_call_s, "unit": "group-updates/s", "cores": 1, "kind": "oracle",
+        "sample": f"exact-mode (fp64) oracle, one call of U={wl.U} updates on a contiguous slice of {P} of "
+                  f"{wl.P} elements in {t:.2f} s, scaled by {wl.P / P:.1f}x (elements are independent)",
+        "gbps": wl.algorithmic_bytes_per_call() / full_call_s / 1e9,
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on one GPU; --gpus must be 1 "
+                         "(the update shards by element across parameter-server GPUs, no multi-GPU path here)\n")
+        sys.exit(2)
+    import torch
+    import paper_2512_09685_amd as star
+    import workloads
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(1)
+    star.load_library()
+    star.star_set_kernel({"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE}[a.kernel])
+    head_wl = workloads.WORKLOADS[a.workload]
+    head = measure(head_wl, a.steps, a.warmup, torch, star, workloads)
+    per_config = []
+    if not a.only:
+        for name in workloads.ORDER:
+            if name == a.workload:
+                per_config.append(head)
+            else:
+                per_config.append(measure(workloads.WORKLOADS[name], max(3, min(a.steps, 10)), min(a.warmup, 2),
+                                          torch, star, workloads))
+    out = {
+        "metric": "group_updates_per_s",
+        "value": head["group_updates_per_s"],
+        "unit": "group-updates/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": a.workload, "P": head_wl.P, "W": head_wl.W, "U": head_wl.U * head_wl.calls,
+                   "grad_dtype": head_wl.grad_dtype, "norms": head_wl.norms, "kernel_choice": a.kernel},
+        "hbm_gbps": head["hbm_gbps"],
+        "roofline": {
+            "bound": "hbm", "achieved": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "traffic": None, "kernel": head["kernel"],
+            "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
+            "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "
+                    "norm-finishing kernels that follow each update kernel",
+        },
+    }
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(head_wl, torch, workloads)
+    if per_config:
+        out["per_config"] = per_config
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
