@@ -34,7 +34,7 @@ def parse():
 def kernel_label(star, wl, us):
     k, fs, fa = star.star_plan_choice(wl.W, us, lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay,
                                       wmode=wl.wmode, want_norms=wl.norms)
-    dt = "RowF32" if wl.grad_dtype == "f32" else ("RowBf16x4" if wl.norms and wl.W <= 16 else "RowBf16x8")
+    dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
     if k == star.KERNEL_AFFINE:
         return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
     return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa

@@ -188,7 +188,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     int device = 0, num_cu = 1;
     st = device_info(&device, &num_cu);
     if (st != STAR_OK) return st;
-    const int grid_cap = num_cu * star::kMaxBlocksPerCU;
+    const int grid_cap = star::kGridCap;
 
     const int grad_bytes = grad_dtype == STAR_F32 ? 4 : 2;
     const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice);
@@ -358,8 +358,7 @@ star_status star_set_kernel(int32_t kernel) {
 size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U) {
     if (P <= 0 || W < 1 || W > STAR_MAX_WORKERS || U <= 0) return 0;
     const int Wp = star::padded_rows(W);
-    // the grid never exceeds 8 blocks on each of at most 256 compute units
-    const int grid_cap = 256 * star::kMaxBlocksPerCU;
+    const int grid_cap = star::kGridCap;
     return std::max<size_t>(table_layout(U, Wp).total, 64 * 1024) +
            sizeof(double) * partial_doubles_needed(Wp, U, grid_cap);
 }

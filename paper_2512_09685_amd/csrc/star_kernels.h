@@ -10,7 +10,7 @@
 namespace star {
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
-constexpr int kMaxBlocksPerCU = 8;   // 32 waves per CU is the hardware ceiling
+constexpr int kGridCap = 4096;       // most workgroups a norm-reducing launch uses (sizes the partial buffer)
 
 struct RowPtrs {
     const void* p[STAR_MAX_WORKERS];

@@ -1,9 +1,13 @@
 // gfx950 kernels for the group-synchronous parameter update.
 //
-// Layout: every buffer is a flat array of P elements; thread t of the grid
-// owns "chunks" t, t+T, t+2T, ... of VEC consecutive elements (T = threads in
-// the grid), so a wave reads 64 consecutive 16-byte pieces of each row: whole
-// cache lines, every byte used once.  Each gradient row, params and momentum
+// Layout: every buffer is a flat array of P elements, cut into "chunks" of VEC
+// consecutive elements.  A wave works on 64 consecutive chunks, so it reads 64
+// consecutive 16-byte pieces of each row: whole cache lines, every byte used
+// once.  Workgroups are mapped to chunks in "spans": G consecutive workgroups
+// sweep one contiguous span of G*K tiles together (tile = 256 chunks), each
+// taking every G-th tile, so that at any moment the running workgroups touch a
+// narrow, advancing window of every row (DRAM pages stay open) while each
+// workgroup still lives for K tiles (one norm reduction per K tiles).  Each gradient row, params and momentum
 // are read once per call; params and momentum are written once.  All state of
 // an element lives in registers between the load and the store.
 //
@@ -19,6 +23,8 @@
 #include <hip/hip_runtime.h>
 
 #include "star_kernels.h"
+
+#include <algorithm>
 
 namespace star {
 
@@ -49,9 +55,9 @@ __device__ __forceinline__ float bf16_of(uint32_t dword) {
     return (K & 1) ? __uint_as_float(dword & 0xffff0000u) : __uint_as_float(dword << 16);
 }
 
-struct RowBf16x8 {
-    static constexpr int VEC = 8;
-    typedef u32x4 vec;
+struct RowBf16x4 {
+    static constexpr int VEC = 4;
+    typedef u32x2 vec;
     static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
         return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
     }
@@ -62,18 +68,13 @@ struct RowBf16x8 {
     }
 };
 
-struct RowBf16x4 {
-    static constexpr int VEC = 4;
-    typedef u32x2 vec;
-    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
-        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
-    }
-    template <int K>
-    static __device__ __forceinline__ float get(const vec& x) { return bf16_of<K>(x[K >> 1]); }
-    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
-        return RowBf16x8::load1(row, j);
-    }
-};
+// Streaming (non-temporal) 16-byte store.  The empty asm pins the value in
+// vector registers at this point; without it the optimiser re-forms the store
+// from the scalar results and the non-temporal hint is lost.
+__device__ __forceinline__ void store_streaming(f32x4 x, f32x4* dst) {
+    asm volatile("" : "+v"(x));
+    __builtin_nontemporal_store(x, dst);
+}
 
 // ---------------------------------------------------------------- wave64 sum
 // Sum over the 64 lanes with data-parallel-primitive moves; the total lands in
@@ -104,6 +105,21 @@ __device__ __forceinline__ void static_for(F&& f) {
         f(std::integral_constant<int, I>{});
         static_for<I + 1, N>(f);
     }
+}
+
+// ---------------------------------------------------------------- workgroup -> tile mapping
+// Workgroup b handles items first, first+step, ... (at most K of them, below n).
+struct Span {
+    int64_t first, step;
+    int32_t K;
+};
+__device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
+    const int64_t G = span_g;
+    Span s;
+    s.first = ((int64_t)(blockIdx.x / span_g) * G * span_k + (blockIdx.x % span_g)) * kBlock + threadIdx.x;
+    s.step = G * kBlock;
+    s.K = span_k;
+    return s;
 }
 
 // ================================================================= affine kernel
@@ -138,27 +154,33 @@ __device__ __forceinline__ void gram_step(float (&acc)[W * (W + 1) / 2], const f
 template <int W, class R, bool UPDATE, bool GRAM>
 __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
-                                                     const int vec_ok, double* __restrict__ partials) {
+                                                     const int vec_ok, const int span_g, const int span_k,
+                                                     double* __restrict__ partials) {
     constexpr int VEC = R::VEC;
     constexpr int NG = W * (W + 1) / 2;
     float acc[GRAM ? NG : 1];
 #pragma unroll
     for (int e = 0; e < (GRAM ? NG : 1); ++e) acc[e] = 0.0f;
 
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    const int64_t gtid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const Span span = make_span(span_g, span_k);
     const int64_t nchunk = vec_ok ? P / VEC : 0;
 
-    for (int64_t c = gtid; c < nchunk; c += stride) {
+    int64_t c = span.first;
+    for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
         typename R::vec g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = R::load(rows.p[w], c);
-        f32x4 pv[VEC / 4], vv[VEC / 4];
+        float pe[VEC], ve[VEC];
         if constexpr (UPDATE) {
 #pragma unroll
             for (int q = 0; q < VEC / 4; ++q) {
-                pv[q] = reinterpret_cast<const f32x4*>(params)[c * (VEC / 4) + q];
-                vv[q] = reinterpret_cast<const f32x4*>(momentum)[c * (VEC / 4) + q];
+                const f32x4 pq = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(params) + c * (VEC / 4) + q);
+                const f32x4 vq = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(momentum) + c * (VEC / 4) + q);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    pe[4 * q + k] = pq[k];
+                    ve[4 * q + k] = vq[k];
+                }
             }
         }
         static_for<0, VEC>([&](auto kc) {
@@ -168,25 +190,25 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
                 constexpr int Wi = decltype(wc)::value;
                 ge[Wi] = R::template get<K>(g[Wi]);
             });
-            if constexpr (UPDATE) {
-                float pe = pv[K / 4][K % 4], ve = vv[K / 4][K % 4];
-                aff_step<W>(pe, ve, ge, cf);
-                pv[K / 4][K % 4] = pe;
-                vv[K / 4][K % 4] = ve;
-            }
+            if constexpr (UPDATE) aff_step<W>(pe[K], ve[K], ge, cf);
             if constexpr (GRAM) gram_step<W>(acc, ge);
         });
         if constexpr (UPDATE) {
 #pragma unroll
             for (int q = 0; q < VEC / 4; ++q) {
-                reinterpret_cast<f32x4*>(params)[c * (VEC / 4) + q] = pv[q];
-                reinterpret_cast<f32x4*>(momentum)[c * (VEC / 4) + q] = vv[q];
+                f32x4 pq = {pe[4 * q], pe[4 * q + 1], pe[4 * q + 2], pe[4 * q + 3]};
+                f32x4 vq = {ve[4 * q], ve[4 * q + 1], ve[4 * q + 2], ve[4 * q + 3]};
+                store_streaming(pq, reinterpret_cast<f32x4*>(params) + c * (VEC / 4) + q);
+                store_streaming(vq, reinterpret_cast<f32x4*>(momentum) + c * (VEC / 4) + q);
             }
         }
     }
     // elements not covered by whole chunks (the ragged end, or everything when
     // some buffer is not 16-byte aligned): same arithmetic, one element at a time
-    for (int64_t j = nchunk * VEC + gtid; j < P; j += stride) {
+    const int64_t nrest = P - nchunk * VEC;
+    int64_t r = span.first;
+    for (int k = 0; k < span.K && r < nrest; ++k, r += span.step) {
+        const int64_t j = nchunk * VEC + r;
         float ge[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) ge[w] = R::load1(rows.p[w], j);
@@ -258,7 +280,8 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const float* __restrict__ t_lr,
                                                      const uint32_t* __restrict__ t_mask, const int U,
                                                      const float mu, const float wd, const int64_t P,
-                                                     const int vec_ok, double* __restrict__ partials) {
+                                                     const int vec_ok, const int span_g, const int span_k,
+                                                     double* __restrict__ partials) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
     extern __shared__ float lds[];
     float* s_coef = lds;
@@ -275,18 +298,18 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
         for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
     __syncthreads();
 
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    const int64_t gtid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const Span span = make_span(span_g, span_k);
     const int64_t nchunk = vec_ok ? P / 4 : 0;
 
-    for (int64_t c = gtid; c < nchunk; c += stride) {
+    int64_t c = span.first;
+    for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
         typename R::vec raw[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) raw[w] = R::load(rows.p[w], c);
         float p[4] = {0, 0, 0, 0}, v[4] = {0, 0, 0, 0};
         if constexpr (UPDATE) {
-            const f32x4 pv = reinterpret_cast<const f32x4*>(params)[c];
-            const f32x4 vv = reinterpret_cast<const f32x4*>(momentum)[c];
+            const f32x4 pv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(params) + c);
+            const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(momentum) + c);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 p[k] = pv[k];
@@ -309,11 +332,14 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                 pv[k] = p[k];
                 vv[k] = v[k];
             }
-            reinterpret_cast<f32x4*>(params)[c] = pv;
-            reinterpret_cast<f32x4*>(momentum)[c] = vv;
+            store_streaming(pv, reinterpret_cast<f32x4*>(params) + c);
+            store_streaming(vv, reinterpret_cast<f32x4*>(momentum) + c);
         }
     }
-    for (int64_t j = nchunk * 4 + gtid; j < P; j += stride) {
+    const int64_t nrest = P - nchunk * 4;
+    int64_t r = span.first;
+    for (int k = 0; k < span.K && r < nrest; ++k, r += span.step) {
+        const int64_t j = nchunk * 4 + r;
         float g[W][4];
 #pragma unroll
         for (int w = 0; w < W; ++w) {
@@ -397,19 +423,33 @@ int padded_rows(int Wc) {
 
 namespace {
 
-int resident_blocks(const void* kernel, size_t lds_bytes) {
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, lds_bytes) != hipSuccess || n < 1) n = 1;
-    return n > kMaxBlocksPerCU ? kMaxBlocksPerCU : n;
-}
+// Launch geometry: G workgroups per span, K tiles per workgroup, and the grid.
+struct Geometry {
+    int grid, span_g, span_k;
+};
 
-int pick_grid(int64_t P, int elems_per_thread, int num_cu, int blocks_per_cu, int grid_cap) {
-    const int64_t per_block = (int64_t)kBlock * elems_per_thread;
-    int64_t need = (P + per_block - 1) / per_block;
-    int64_t g = (int64_t)num_cu * blocks_per_cu;
-    if (g > grid_cap) g = grid_cap;
-    if (need < g) g = need;
-    return g < 1 ? 1 : (int)g;
+// items = chunks (or single elements when the buffers are not 16-byte aligned).
+// A kernel that ends with a per-workgroup norm reduction runs one long-lived
+// workgroup per compute unit, all sweeping the shard as a single span; the
+// others get one tile per workgroup, dispatched in address order.  Both keep
+// the set of addresses in flight a narrow window that advances through every
+// row together, which is what measured fastest on MI355X for this mix of 16+
+// read streams and two read-modify-write streams.
+Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int num_cu, int grid_cap) {
+    const int64_t items = vec_ok ? std::max<int64_t>(P / vec, P % vec) : P;
+    const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
+    Geometry g;
+    if (reduces) {
+        g.span_g = (int)std::min<int64_t>(std::min(num_cu, grid_cap), tiles);
+        g.span_k = 0x7fffffff;
+        g.grid = g.span_g;
+    } else {
+        const int64_t max_grid = 0x7fffffff;
+        g.span_g = 1;
+        g.span_k = (int)((tiles + max_grid - 1) / max_grid);   // 1 unless the shard is absurdly long
+        g.grid = (int)((tiles + g.span_k - 1) / g.span_k);
+    }
+    return g;
 }
 
 size_t seq_lds_bytes(int W, int U, bool norms) {
@@ -420,21 +460,20 @@ template <int W, class R, bool UPDATE, bool NORMS>
 hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = seq_kernel<W, R, UPDATE, NORMS>;
     const size_t lds = seq_lds_bytes(W, a.U, NORMS);
-    const int grid = pick_grid(a.P, 4, num_cu, resident_blocks(reinterpret_cast<const void*>(kern), lds), grid_cap);
-    *grid_out = grid;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
-                       a.U, a.mu, a.wd, a.P, a.vec_ok, a.partials);
+    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap);
+    *grid_out = g.grid;
+    hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
+                       a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.partials);
     return hipGetLastError();
 }
 
 template <int W, class R, bool UPDATE, bool GRAM>
 hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
-    static const int blocks_per_cu = resident_blocks(reinterpret_cast<const void*>(kern), 0);
-    const int grid = pick_grid(a.P, R::VEC, num_cu, blocks_per_cu, grid_cap);
-    *grid_out = grid;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
-                       a.partials);
+    const Geometry g = pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
+    *grid_out = g.grid;
+    hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
+                       g.span_g, g.span_k, a.partials);
     return hipGetLastError();
 }
 
@@ -456,7 +495,6 @@ hipError_t launch_aff_w(int dtype, bool update, bool gram, const AffArgs& a, int
                         int* grid_out, hipStream_t s) {
     if constexpr (W <= 16) {
         if (gram) {
-            // with the W(W+1)/2 accumulators live, 4 elements per thread keep the kernel at two waves per SIMD
             if (dtype == STAR_F32) {
                 if (update) return launch_aff_t<W, RowF32, true, true>(a, num_cu, grid_cap, grid_out, s);
                 return launch_aff_t<W, RowF32, false, true>(a, num_cu, grid_cap, grid_out, s);
@@ -467,7 +505,7 @@ hipError_t launch_aff_w(int dtype, bool update, bool gram, const AffArgs& a, int
     }
     if (gram || !update) return hipErrorInvalidValue;
     if (dtype == STAR_F32) return launch_aff_t<W, RowF32, true, false>(a, num_cu, grid_cap, grid_out, s);
-    return launch_aff_t<W, RowBf16x8, true, false>(a, num_cu, grid_cap, grid_out, s);
+    return launch_aff_t<W, RowBf16x4, true, false>(a, num_cu, grid_cap, grid_out, s);
 }
 
 }  // namespace
