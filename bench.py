@@ -28,6 +28,9 @@ def parse():
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per-config table)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine"])
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the timed region, run three plain device copies of 1 GiB (a known-size kernel to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     return ap.parse_args()
 
 
@@ -150,6 +153,14 @@ def main():
     star.load_library()
     star.star_set_kernel({"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE}[a.kernel])
     head_wl = workloads.WORKLOADS[a.workload]
+    if a.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     head = measure(head_wl, a.steps, a.warmup, torch, star, workloads)
     per_config = []
     if not a.only:

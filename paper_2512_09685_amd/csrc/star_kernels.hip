@@ -123,6 +123,8 @@ __device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
 }
 
 // ================================================================= affine kernel
+constexpr int kGramFold = 64;  // tiles between folds of the pairwise-product accumulators (power of two)
+
 template <int W>
 __device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W], const AffCoef& cf) {
     // increment of p first, one final add: p is perturbed by one rounding of p itself
@@ -161,12 +163,31 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
     float acc[GRAM ? NG : 1];
 #pragma unroll
     for (int e = 0; e < (GRAM ? NG : 1); ++e) acc[e] = 0.0f;
+    // Second-level sums, one private LDS slot per thread and pair.  The register
+    // accumulators are folded into them every kGramFold tiles, so no fp32 chain
+    // of products is longer than 4*kGramFold terms: long chains of squares of
+    // short-mantissa (bf16) values round down systematically, about 1e-9 per
+    // term, because the low bits of a square are not uniformly distributed.
+    __shared__ float fold[GRAM ? NG * kBlock : 1];
+    if constexpr (GRAM) {
+#pragma unroll
+        for (int e = 0; e < NG; ++e) fold[e * kBlock + threadIdx.x] = 0.0f;
+    }
 
     const Span span = make_span(span_g, span_k);
     const int64_t nchunk = vec_ok ? P / VEC : 0;
 
     int64_t c = span.first;
     for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
+        if constexpr (GRAM) {
+            if ((k & (kGramFold - 1)) == kGramFold - 1) {
+#pragma unroll
+                for (int e = 0; e < NG; ++e) {
+                    fold[e * kBlock + threadIdx.x] += acc[e];
+                    acc[e] = 0.0f;
+                }
+            }
+        }
         typename R::vec g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = R::load(rows.p[w], c);
@@ -226,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
         for (int e = 0; e < NG; ++e) {
-            const float s = wave_sum_to_lane63(acc[e]);
+            const float s = wave_sum_to_lane63(acc[e] + fold[e * kBlock + threadIdx.x]);
             if (lane == 63) wave_part[wave][e] = s;
         }
         __syncthreads();
@@ -394,20 +415,33 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const double* __restrict
     }
 }
 
+// One workgroup per update u: n_u^2 = sum over pairs (a <= b) of c_a c_b Gamma_ab (off-diagonal pairs twice),
+// each thread one pair, then a fixed-order tree sum in double.
 __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __restrict__ gamma,
                                                             const double* __restrict__ coef, const int U,
                                                             const int W, float* __restrict__ norms_out) {
-    const int u = blockIdx.x * kBlock + threadIdx.x;
-    if (u >= U) return;
+    __shared__ double s_part[kBlock];
+    const int u = blockIdx.x;
     const double* c = coef + (int64_t)u * W;
+    const int ng = W * (W + 1) / 2;
     double s = 0.0;
-    int e = 0;
-    for (int a = 0; a < W; ++a)
-        for (int b = a; b < W; ++b, ++e) {
-            const double t = c[a] * c[b] * gamma[e];
-            s += (a == b) ? t : 2.0 * t;
+    for (int e = threadIdx.x; e < ng; e += kBlock) {
+        int a = 0, rem = e;
+        while (rem >= W - a) {
+            rem -= W - a;
+            ++a;
         }
-    norms_out[u] = (float)sqrt(s > 0.0 ? s : 0.0);
+        const int b = a + rem;
+        const double t = c[a] * c[b] * gamma[e];
+        s += (a == b) ? t : 2.0 * t;
+    }
+    s_part[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && u < U) norms_out[u] = (float)sqrt(s_part[0] > 0.0 ? s_part[0] : 0.0);
 }
 
 __global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, const int64_t n, const float value) {
@@ -555,7 +589,7 @@ hipError_t launch_reduce(const double* partials, int n_out, int grid, double* su
 hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int Wp, float* norms_out,
                              hipStream_t s) {
     if (U < 1) return hipSuccess;
-    hipLaunchKernelGGL(gram_norms_kernel, dim3((U + kBlock - 1) / kBlock), dim3(kBlock), 0, s, gamma, coef, U, Wp,
+    hipLaunchKernelGGL(gram_norms_kernel, dim3(U), dim3(kBlock), 0, s, gamma, coef, U, Wp,
                        norms_out);
     return hipGetLastError();
 }

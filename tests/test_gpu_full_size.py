@@ -1,0 +1,105 @@
+"""Parity at the five workloads' full sizes, in the configuration bench.py times.
+
+The oracle cannot run 1e8 elements x 64 updates in test time, but every element
+is independent, so the updated state is checked on sampled elements (head, the
+ragged tail, windows at odd offsets): the oracle is run on exactly those
+elements.  Norms couple all elements; they are checked (a) against the oracle
+over the full shard for the two smallest groups of the call, and (b) for every
+update against the library's other, independent norm route (direct sum of
+squares versus pairwise products), which must agree far inside the tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_09685_amd as star
+import workloads
+from oracle import star_oracle as so
+from gpu_util import TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_indices(P, rng, window=2048, n_mid=6):
+    parts = [np.arange(0, min(window, P)), np.arange(max(0, P - window - 3), P)]
+    for _ in range(n_mid):
+        lo = int(rng.integers(0, max(1, P - window))) | 1          # odd offsets: not chunk aligned
+        parts.append(np.arange(lo, min(P, lo + window)))
+    return np.unique(np.concatenate(parts))
+
+
+def rows_at(rows, idx_dev):
+    out = []
+    for r in rows:
+        x = r[idx_dev].cpu()
+        out.append(x.view(torch.int16).numpy().view(np.uint16).copy() if x.dtype == torch.bfloat16 else x.numpy())
+    return out
+
+
+@pytest.mark.parametrize("name", workloads.ORDER)
+def test_full_size_workload(name):
+    wl = workloads.WORKLOADS[name]
+    print(f"full-size {name}: P={wl.P} W={wl.W} U={wl.U}x{wl.calls} {wl.grad_dtype}", flush=True)
+    rng = np.random.default_rng(123)
+    idx = sample_indices(wl.P, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    p = workloads.make_params(wl, 0, "cuda")
+    v = workloads.make_momentum(wl, "cuda")
+    ep, ev = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    tol = TOL[wl.grad_dtype]
+    rows = None
+    for call in range(wl.calls):
+        if rows is None or wl.fresh_grads_per_call:
+            rows = None                                     # free the previous set first
+            rows = workloads.make_grad_rows(wl, 0, call, "cuda")
+        s = workloads.make_update_stream(wl, 0, call)
+        us = star.UpdateStream(s["offsets"], s["members"], s["staleness"])
+        norms = torch.zeros(wl.U, device="cuda")            # asked for on every workload here
+        star.star_group_update(p, v, rows, us, norms_out=norms, **hp)
+        torch.cuda.synchronize()
+        # state on the sampled elements
+        ep, ev, _ = so.group_update(ep, ev, rows_at(rows, idx_dev), s["offsets"], s["members"],
+                                    staleness=s["staleness"], **hp)
+        e_p = so.max_rel_err(p[idx_dev].cpu().numpy(), ep)
+        e_v = so.max_rel_err(v[idx_dev].cpu().numpy(), ev)
+        print(f"  call {call}: sampled {idx.size} elements, err params {e_p:.3g} momentum {e_v:.3g}", flush=True)
+        assert e_p <= tol and e_v <= tol
+        # norms: second route on the GPU for all updates
+        n_gpu = norms.cpu().numpy()
+        star.star_set_kernel(star.KERNEL_SEQ)
+        try:
+            norms2 = torch.zeros(wl.U, device="cuda")
+            star.star_group_norms(rows, us, norms2, wmode=wl.wmode)
+            torch.cuda.synchronize()
+        finally:
+            star.star_set_kernel(star.KERNEL_AUTO)
+        e_routes = float(np.max(np.abs(n_gpu - norms2.cpu().numpy()) / norms2.cpu().numpy()))
+        # norms: oracle over the whole shard for the two smallest groups
+        sizes = np.diff(s["offsets"])
+        pick = np.argsort(sizes, kind="stable")[:2]
+        offs, mem, st = [0], [], []
+        for u in pick:
+            lo, hi = s["offsets"][u], s["offsets"][u + 1]
+            mem += list(s["members"][lo:hi])
+            st += list(s["staleness"][lo:hi]) if s["staleness"] is not None else [0] * (hi - lo)
+            offs.append(len(mem))
+        need = sorted(set(mem))
+        host_rows = [None] * wl.W
+        for w in range(wl.W):
+            if w in need:
+                x = rows[w].cpu()
+                host_rows[w] = (x.view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16
+                                else x.numpy())
+            else:                                        # never read by the oracle for these groups
+                host_rows[w] = host_rows[need[0]] if host_rows[need[0]] is not None else None
+        first = next(r for r in host_rows if r is not None)
+        host_rows = [r if r is not None else first for r in host_rows]
+        en = so.group_norms(host_rows, offs, mem, wmode=wl.wmode, staleness=st)
+        e_n = float(np.max(np.abs(n_gpu[pick] - en) / en))
+        print(f"  call {call}: norms vs oracle (updates {pick.tolist()}, sizes {sizes[pick].tolist()}) {e_n:.3g}; "
+              f"two GPU routes differ by {e_routes:.3g}", flush=True)
+        assert e_n <= tol and e_routes <= min(tol, 2e-6)
+        del host_rows, norms, norms2
+    del p, v, rows
+    torch.cuda.empty_cache()
