@@ -132,6 +132,25 @@ star_status star_group_norms(const void *const *grad_rows, star_dtype grad_dtype
                              const star_updates *upd, int32_t wmode, float *norms_out, void *hip_stream);
 
 /*
+ * Aggregation without the optimizer step: for every group u,
+ *     out_rows[u][j] = sum_{w in G_u} c_{u,w} g_w[j]            (j = 0 .. P-1)
+ * This is what a parent computes from its children's gradients and its own
+ * before broadcasting in the all-reduce architecture (Section 4.2, "All-reduce
+ * architecture"), and what a node of the communication tree forwards upward
+ * (Section 4.4.2, tree-based communication).  One pass: every referenced row is
+ * read once, every output written once.
+ *   out_rows  : host array of U device pointers, each P elements of out_dtype
+ *               (fp32, or bf16 rounded to nearest even).  Outputs must not
+ *               alias the gradient rows or each other.
+ *   norms_out : device float[U] (|| out_u ||_2 computed from the fp32 sums,
+ *               before any rounding to bf16), or NULL.
+ * Other arguments and all conventions as for star_group_update.
+ */
+star_status star_group_reduce(void *const *out_rows, star_dtype out_dtype, const void *const *grad_rows,
+                              star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd, int32_t wmode,
+                              float *norms_out, void *hip_stream);
+
+/*
  * Host-only: the U updates of a stream written as one affine map,
  *     (p_U, v_U)^T = M (p_0, v_0)^T + B (g_0 .. g_{W-1})^T,
  * composed in double precision.  M is row-major 2x2, B row-major 2xW.  Touches

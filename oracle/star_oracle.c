@@ -181,6 +181,34 @@ int oracle_group_norms(const void *const *rows, int grad_dtype, int64_t P, int32
 }
 
 /*
+ * Aggregation without the optimizer step (the sum a parent forms from its
+ * children's gradients and its own in the all-reduce architecture, Section 4.2;
+ * the sum a tree node forwards upward, Section 4.4.2):
+ *     out[u*P + j] = sum over listed members m of coef(u,m) * g_member[j].
+ * norms_out (may be NULL) receives || out_u ||_2.
+ */
+int oracle_group_reduce(double *out, const void *const *rows, int grad_dtype, int64_t P, int32_t W,
+                        const oracle_updates *up, int32_t wmode, double *norms_out)
+{
+    int rc = check_stream(up, W);
+    if (rc) return rc;
+    for (int32_t u = 0; u < up->U; ++u) {
+        const int32_t lo = up->offsets[u];
+        const int32_t y = up->offsets[u + 1] - lo;
+        double sumsq = 0.0;
+        for (int64_t j = 0; j < P; ++j) {
+            double gbar = 0.0;
+            for (int32_t m = 0; m < y; ++m)
+                gbar += member_coef(up, wmode, lo + m, y) * grad_at(rows[up->members[lo + m]], grad_dtype, j);
+            out[(int64_t)u * P + j] = gbar;
+            sumsq += gbar * gbar;
+        }
+        if (norms_out) norms_out[u] = sqrt(sumsq);
+    }
+    return 0;
+}
+
+/*
  * Stepwise-fp32 mode: what a literal fp32 parameter server produces.  Every
  * product and sum is rounded to fp32 (this file is compiled with
  * -ffp-contract=off, so no fused multiply-add), members are taken in

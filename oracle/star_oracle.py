@@ -53,7 +53,7 @@ def _load():
         # broken build of the oracle (on the CPU) to show that the pins catch it.
         _lib = ctypes.CDLL(os.environ.get("STAR_ORACLE_LIB") or build())
         for name in ("oracle_group_update", "oracle_group_update_f64", "oracle_group_update_f32step",
-                     "oracle_group_norms"):
+                     "oracle_group_norms", "oracle_group_reduce"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -143,6 +143,20 @@ def group_norms(rows: Sequence[np.ndarray], offsets, members, *, wmode: str = "m
     if rc:
         raise ValueError(f"oracle rejected the update stream (code {rc})")
     return norms
+
+
+def group_reduce(rows: Sequence[np.ndarray], offsets, members, *, wmode: str = "mean", staleness=None, coeff=None,
+                 want_norms: bool = False):
+    """Weighted sum of every group's rows: float64 array [U, P] (and norms [U] if asked)."""
+    lib = _load()
+    m = _Marshal(rows, offsets, members, staleness, coeff, None)
+    out = np.zeros((max(m.U, 0), m.P), dtype=np.float64)
+    norms = np.zeros(max(m.U, 0), dtype=np.float64) if want_norms else None
+    rc = lib.oracle_group_reduce(_ptr(out), m.rowptr, m.dtype, ctypes.c_int64(m.P), m.W, ctypes.byref(m.upd),
+                                 _WMODES[wmode], _ptr(norms))
+    if rc:
+        raise ValueError(f"oracle rejected the update stream (code {rc})")
+    return (out, norms) if want_norms else out
 
 
 def max_rel_err(x: np.ndarray, ref: np.ndarray) -> float:

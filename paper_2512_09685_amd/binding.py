@@ -60,6 +60,8 @@ def load_library():
     lib.star_group_update.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp]
     lib.star_group_norms.restype = ctypes.c_int
     lib.star_group_norms.argtypes = [vp, ctypes.c_int, i64, i32, vp, i32, vp, vp]
+    lib.star_group_reduce.restype = ctypes.c_int
+    lib.star_group_reduce.argtypes = [vp, ctypes.c_int, vp, ctypes.c_int, i64, i32, vp, i32, vp, vp]
     lib.star_plan_affine.restype = ctypes.c_int
     lib.star_plan_affine.argtypes = [i32, vp, vp, vp, vp]
     lib.star_plan_choice.restype = ctypes.c_int
@@ -170,6 +172,24 @@ def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, w
     _check(lib.star_group_norms(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c),
                                 _WMODES[wmode] if isinstance(wmode, str) else wmode, norms_out.data_ptr(),
                                 _stream_handle(stream)))
+
+
+def star_group_reduce(out_rows: Sequence, grad_rows: Sequence, updates: UpdateStream, *, wmode="mean", norms_out=None,
+                      stream=None) -> None:
+    """out_rows[u] = weighted sum of group u's gradient rows (float32 or bfloat16
+    CUDA tensors [P], one per group), enqueued on ``stream``."""
+    import torch
+    lib = load_library()
+    P = int(next(r for r in grad_rows if r is not None).shape[0])
+    ptrs, dt = _rows(grad_rows, P)
+    if len(out_rows) != updates.U:
+        raise ValueError("one output row per group is required")
+    optrs, odt = _rows(out_rows, P)
+    if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
+        raise ValueError("norms_out must hold U floats")
+    _check(lib.star_group_reduce(optrs, odt, ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c),
+                                 _WMODES[wmode] if isinstance(wmode, str) else wmode,
+                                 None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
 
 
 def star_plan_affine(W: int, updates: UpdateStream, *, lr: float, momentum_coef: float, weight_decay: float = 0.0,

@@ -132,9 +132,9 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Table layout in a slot (all offsets 256-byte aligned):
-//   coef_f32 [U][Wp] | lr_f32 [U] | mask_u32 [U] | coef_f64 [U][Wp]
+//   coef_f32 [U][Wp] | lr_f32 [U] | mask_u32 [U] | coef_f64 [U][Wp] | out pointers [U]
 struct TableLayout {
-    size_t coef32, lr32, mask, coef64, total;
+    size_t coef32, lr32, mask, coef64, outptr, total;
 };
 
 TableLayout table_layout(int U, int Wp) {
@@ -144,13 +144,14 @@ TableLayout table_layout(int U, int Wp) {
     t.lr32 = o;   o = align_up(o + sizeof(float) * (size_t)U, 256);
     t.mask = o;   o = align_up(o + sizeof(uint32_t) * (size_t)U, 256);
     t.coef64 = o; o = align_up(o + sizeof(double) * (size_t)U * Wp, 256);
+    t.outptr = o; o = align_up(o + sizeof(void*) * (size_t)U, 256);
     t.total = o;
     return t;
 }
 
 size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
     const size_t ng = (size_t)Wp * (Wp + 1) / 2;
-    const size_t useq = (size_t)std::min(U, star::seq_max_updates(Wp, true));
+    const size_t useq = (size_t)std::min(U, std::max(star::seq_max_updates(Wp, true), star::reduce_max_updates(Wp, true)));
     // per-block partials of the larger of the two routes, plus the reduced Gram matrix
     return std::max(ng, useq) * (size_t)grid_cap + ng;
 }
@@ -301,6 +302,90 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     return STAR_OK;
 }
 
+// Body of star_group_reduce.
+star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* grad_rows, int grad_dtype, int64_t P,
+                       int32_t W, const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
+    g_err.clear();
+    if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
+    if (!grad_rows) return set_err(STAR_ERR_NULL, "grad_rows is NULL");
+    if (!out_rows && upd->U > 0) return set_err(STAR_ERR_NULL, "out_rows is NULL");
+    if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
+    if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
+    if (out_dtype != STAR_F32 && out_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown output dtype");
+    const bool want_norms = norms_out != nullptr;
+    star::Plan plan;
+    std::string msg;
+    star_status st = star::build_plan(W, upd, nullptr, wmode, want_norms, &plan, &msg);
+    if (st != STAR_OK) return set_err(st, msg);
+    const int U = plan.U, Wc = plan.Wc;
+    if (P > 0) {
+        for (int k = 0; k < Wc; ++k)
+            if (!grad_rows[plan.row_of[k]]) return set_err(STAR_ERR_NULL, "a gradient row used by a group is NULL");
+        for (int u = 0; u < U; ++u)
+            if (!out_rows[u]) return set_err(STAR_ERR_NULL, "an output row is NULL");
+    }
+    if (U == 0) return STAR_OK;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (P == 0) {
+        if (want_norms) STAR_HIP(star::launch_fill(norms_out, U, 0.0f, stream));
+        return STAR_OK;
+    }
+    int device = 0, num_cu = 1;
+    st = device_info(&device, &num_cu);
+    if (st != STAR_OK) return st;
+    const int grid_cap = star::kGridCap;
+    const int Wp = star::padded_rows(Wc);
+    star::RowPtrs rows;
+    bool vec_ok = true;
+    for (int k = 0; k < STAR_MAX_WORKERS; ++k) {
+        rows.p[k] = grad_rows[plan.row_of[std::min(k, Wc - 1)]];
+        if (k < Wc && !aligned16(rows.p[k])) vec_ok = false;
+    }
+    for (int u = 0; u < U; ++u)
+        if (!aligned16(out_rows[u])) vec_ok = false;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    const TableLayout lay = table_layout(U, Wp);
+    Slot* slot = nullptr;
+    st = acquire_slot(device, lay.total, want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
+    if (st != STAR_OK) return st;
+    char* h = static_cast<char*>(slot->host);
+    char* d = static_cast<char*>(slot->dev);
+    float* c32 = reinterpret_cast<float*>(h + lay.coef32);
+    uint32_t* mk = reinterpret_cast<uint32_t*>(h + lay.mask);
+    void** op = reinterpret_cast<void**>(h + lay.outptr);
+    for (int u = 0; u < U; ++u) {
+        for (int k = 0; k < Wp; ++k) c32[(size_t)u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
+        mk[u] = plan.mask[u];
+        op[u] = out_rows[u];
+    }
+    STAR_HIP(hipMemcpyAsync(d, h, lay.total, hipMemcpyHostToDevice, stream));
+    const int umax = star::reduce_max_updates(Wp, want_norms);
+    for (int u0 = 0; u0 < U; u0 += umax) {
+        const int n = std::min(umax, U - u0);
+        star::ReduceArgs a;
+        a.rows = rows;
+        a.coef = reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
+        a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
+        a.out = reinterpret_cast<void* const*>(d + lay.outptr) + u0;
+        a.U = n;
+        a.out_dtype = out_dtype;
+        a.P = P;
+        a.vec_ok = vec_ok ? 1 : 0;
+        a.norms = want_norms ? 1 : 0;
+        a.partials = slot->partials;
+        int grid = 0;
+        hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
+        if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
+        if (want_norms) {
+            e = star::launch_reduce(slot->partials, n, grid, nullptr, norms_out + u0, stream);
+            if (e != hipSuccess) return hip_fail(e, "launch of the norm reduction");
+        }
+    }
+    STAR_HIP(hipEventRecord(slot->done, stream));
+    return STAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -314,6 +399,12 @@ star_status star_group_update(float* params, float* momentum, const void* const*
 star_status star_group_norms(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
                              const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
     return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, hip_stream);
+}
+
+star_status star_group_reduce(void* const* out_rows, star_dtype out_dtype, const void* const* grad_rows,
+                              star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd, int32_t wmode,
+                              float* norms_out, void* hip_stream) {
+    return run_reduce(out_rows, (int)out_dtype, grad_rows, (int)grad_dtype, P, W, upd, wmode, norms_out, hip_stream);
 }
 
 star_status star_plan_affine(int32_t W, const star_updates* upd, const star_hparams* hp, double M[4], double* B) {

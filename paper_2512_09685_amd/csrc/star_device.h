@@ -1,0 +1,142 @@
+// Device-side building blocks shared by the kernel files: row access, streaming
+// stores, the wave64 sum, the workgroup-to-tile mapping and the launch geometry.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <type_traits>
+
+#include "star_kernels.h"
+
+namespace star {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- row access
+// A "row type" says how VEC consecutive gradient elements are fetched with one
+// load and how element k is widened to fp32.
+struct RowF32 {
+    static constexpr int VEC = 4;
+    typedef f32x4 vec;
+    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
+    }
+    template <int K>
+    static __device__ __forceinline__ float get(const vec& x) { return x[K]; }
+    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
+        return reinterpret_cast<const float*>(row)[j];
+    }
+};
+
+// bf16 is the upper half of an fp32: widening is a shift (even element of a
+// dword) or a mask (odd element); exact, infinities and NaNs carried over.
+template <int K>
+__device__ __forceinline__ float bf16_of(uint32_t dword) {
+    return (K & 1) ? __uint_as_float(dword & 0xffff0000u) : __uint_as_float(dword << 16);
+}
+
+struct RowBf16x4 {
+    static constexpr int VEC = 4;
+    typedef u32x2 vec;
+    static __device__ __forceinline__ vec load(const void* row, int64_t chunk) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec*>(row) + chunk);
+    }
+    template <int K>
+    static __device__ __forceinline__ float get(const vec& x) { return bf16_of<K>(x[K >> 1]); }
+    static __device__ __forceinline__ float load1(const void* row, int64_t j) {
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(row)[j] << 16);
+    }
+};
+
+// Streaming (non-temporal) 16-byte store.  The empty asm pins the value in
+// vector registers at this point; without it the optimiser re-forms the store
+// from the scalar results and the non-temporal hint is lost.
+__device__ __forceinline__ void store_streaming(f32x4 x, f32x4* dst) {
+    asm volatile("" : "+v"(x));
+    __builtin_nontemporal_store(x, dst);
+}
+
+// ---------------------------------------------------------------- wave64 sum
+// Sum over the 64 lanes with data-parallel-primitive moves; the total lands in
+// lane 63.  Stages: swap within pairs, within quads, mirror within 8, mirror
+// within 16 (every lane of a 16-lane row now holds the row's sum), then lane 15
+// of rows 0 and 2 is added into rows 1 and 3, and lane 31 into rows 2 and 3.
+// The order of additions is fixed, so the result is reproducible.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_take(float x) {
+    // lanes outside ROW_MASK, or whose source lane is invalid, read 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+
+__device__ __forceinline__ float wave_sum_to_lane63(float x) {
+    x += dpp_take<0xB1, 0xf>(x);   // quad_perm [1,0,3,2]
+    x += dpp_take<0x4E, 0xf>(x);   // quad_perm [2,3,0,1]
+    x += dpp_take<0x141, 0xf>(x);  // row_half_mirror
+    x += dpp_take<0x140, 0xf>(x);  // row_mirror
+    x += dpp_take<0x142, 0xa>(x);  // row_bcast:15 into rows 1, 3
+    x += dpp_take<0x143, 0xc>(x);  // row_bcast:31 into rows 2, 3
+    return x;
+}
+
+// ---------------------------------------------------------------- compile-time loops
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// ---------------------------------------------------------------- workgroup -> tile mapping
+// Workgroup b handles items first, first+step, ... (at most K of them, below n).
+struct Span {
+    int64_t first, step;
+    int32_t K;
+};
+__device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
+    const int64_t G = span_g;
+    Span s;
+    s.first = ((int64_t)(blockIdx.x / span_g) * G * span_k + (blockIdx.x % span_g)) * kBlock + threadIdx.x;
+    s.step = G * kBlock;
+    s.K = span_k;
+    return s;
+}
+
+// ================================================================= host side of a launch
+// Launch geometry: G workgroups per span, K tiles per workgroup, and the grid.
+struct Geometry {
+    int grid, span_g, span_k;
+};
+
+// items = chunks (or single elements when the buffers are not 16-byte aligned).
+// A kernel that ends with a per-workgroup norm reduction runs one long-lived
+// workgroup per compute unit, all sweeping the shard as a single span; the
+// others get one tile per workgroup, dispatched in address order.  Both keep
+// the set of addresses in flight a narrow window that advances through every
+// row together, which is what measured fastest on MI355X for this mix of 16+
+// read streams and two read-modify-write streams.
+inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int num_cu, int grid_cap) {
+    const int64_t items = vec_ok ? std::max<int64_t>(P / vec, P % vec) : P;
+    const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
+    Geometry g;
+    if (reduces) {
+        g.span_g = (int)std::min<int64_t>(std::min(num_cu, grid_cap), tiles);
+        g.span_k = 0x7fffffff;
+        g.grid = g.span_g;
+    } else {
+        const int64_t max_grid = 0x7fffffff;
+        g.span_g = 1;
+        g.span_k = (int)((tiles + max_grid - 1) / max_grid);   // 1 unless the shard is absurdly long
+        g.grid = (int)((tiles + g.span_k - 1) / g.span_k);
+    }
+    return g;
+}
+
+#define STAR_FOR_EACH_W(X)                                                                                    \
+    X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(20) X(24) X(28) \
+    X(32)
+
+}  // namespace star

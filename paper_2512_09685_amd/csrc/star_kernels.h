@@ -77,4 +77,23 @@ hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int
 
 hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
 
+// ---- aggregation without the optimizer step (star_group_reduce)
+struct ReduceArgs {
+    RowPtrs rows;
+    const float* coef;       // device [U][Wp]
+    const uint32_t* mask;    // device [U]
+    void* const* out;        // device array of U output row pointers
+    int32_t U;               // groups in this launch
+    int32_t out_dtype;       // star_dtype of the outputs
+    int64_t P;
+    int32_t vec_ok;          // every row and every output 16-byte aligned
+    int32_t norms;           // also accumulate sum of squares per group
+    double* partials;        // device [U][grid] (norms only)
+};
+
+int reduce_max_updates(int Wp, bool norms);
+
+hipError_t launch_group_reduce(int Wp, int dtype, const ReduceArgs& a, int num_cu, int grid_cap, int* grid_out,
+                               hipStream_t s);
+
 }  // namespace star

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "star.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
-    assert {"star_group_update", "star_group_norms", "star_plan_affine", "star_plan_choice", "star_set_kernel",
+    assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_plan_affine", "star_plan_choice", "star_set_kernel",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
@@ -130,3 +130,19 @@ def test_cost_model_prefers_literal_steps_for_one_update_and_collapse_for_many()
 def test_workspace_bytes_is_modest():
     assert star.star_workspace_bytes(0, 4, 4) == 0
     assert 0 < star.star_workspace_bytes(340_000_000, 16, 64) < 8 << 20
+
+
+def test_group_reduce_argument_checks():
+    lib = star.load_library()
+    us = star.UpdateStream([0, 2], [0, 1])
+    ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
+    outs = (ctypes.c_void_p * 1)(0x9000)
+    call = lambda o, od, r, rd, P, W: lib.star_group_reduce(o, od, r, rd, P, W, ctypes.byref(us.c), 0, None, None)
+    assert call(None, 0, ptrs, 0, 8, 4) == 1          # no outputs
+    assert call(outs, 3, ptrs, 0, 8, 4) == 5          # output dtype
+    assert call(outs, 0, ptrs, 9, 8, 4) == 5          # gradient dtype
+    assert call(outs, 0, None, 0, 8, 4) == 1
+    assert call(outs, 0, ptrs, 0, -2, 4) == 2
+    assert call(outs, 0, ptrs, 0, 8, 1) == 3          # member id 1 outside [0, 1)
+    assert call((ctypes.c_void_p * 1)(None), 0, ptrs, 0, 8, 4) == 1
+    assert call(outs, 0, ptrs, 0, 0, 4) == 0          # empty shard: nothing to do

@@ -446,3 +446,43 @@ def test_empty_stream_and_empty_shard():
     e = np.zeros(0, np.float32)
     p, v, n = so.group_update(e, e, [e], [0, 1], [0], lr=0.1, momentum_coef=0.9, want_norms=True)
     assert p.size == 0 and n.tolist() == [0.0]
+
+
+# ---------------------------------------------------------------- aggregation without the optimizer step
+def test_reduce_hand_values():
+    # rows 0.5 and -0.25: group {0,1} mean 0.125; group {1} -> -0.25; stale weight 1/(1+1) on it -> -0.125
+    rows = [f32([0.5, 1.0]), f32([-0.25, 3.0])]
+    out, n = so.group_reduce(rows, [0, 2, 3], [0, 1, 1], want_norms=True)
+    assert out.tolist() == [[0.125, 2.0], [-0.25, 3.0]]
+    np.testing.assert_allclose(n, [np.hypot(0.125, 2.0), np.hypot(0.25, 3.0)], rtol=1e-15)
+    out = so.group_reduce(rows, [0, 2, 3], [0, 1, 1], wmode="stale", staleness=[0, 0, 1])
+    assert out[1].tolist() == [-0.125, 1.5]
+    out = so.group_reduce(rows, [0, 2], [1, 0], wmode="explicit", coeff=[2.0, 0.5])   # listed order: row 1 gets 2.0
+    assert out[0].tolist() == [-0.25, 6.5]
+
+
+def test_reduce_matches_numpy_and_norms_entry():
+    rng, rows, offs, mem, st, p0, v0 = _setup(21, W=7, P=61, U=9, stale=4)
+    out, n = so.group_reduce(rows, offs, mem, wmode="stale", staleness=st, want_norms=True)
+    R = np.stack(rows).astype(np.float64)
+    for u in range(len(offs) - 1):
+        ids = mem[offs[u]:offs[u + 1]]
+        a = 1.0 / (1.0 + st[offs[u]:offs[u + 1]])
+        np.testing.assert_allclose(out[u], (a[:, None] * R[ids]).sum(axis=0) / len(ids), rtol=0, atol=1e-15)
+        np.testing.assert_allclose(n[u], np.linalg.norm(out[u]), rtol=1e-14)
+    assert np.array_equal(n, so.group_norms(rows, offs, mem, wmode="stale", staleness=st))
+
+
+def test_reduce_feeds_a_plain_sgd_step():
+    # mu = 0, wd = 0: one update is p - lr * (aggregated gradient)
+    rng, rows, offs, mem, st, p0, v0 = _setup(22, U=1)
+    out = so.group_reduce(rows, offs, mem)
+    p, v, _ = so.group_update(p0, v0, rows, offs, mem, lr=0.25, momentum_coef=0.0, mode="f64")
+    np.testing.assert_allclose(p, p0.astype(np.float64) - 0.25 * out[0], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(v, out[0], rtol=0, atol=1e-15)
+
+
+def test_reduce_bf16_rows_and_full_group_mean():
+    bits = [np.array([0x3F00, 0x4000], np.uint16), np.array([0xBE80, 0x3F80], np.uint16)]   # 0.5, 2 | -0.25, 1
+    out = so.group_reduce(bits, [0, 2], [0, 1])
+    assert out[0].tolist() == [0.125, 1.5]
