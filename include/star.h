@@ -124,6 +124,20 @@ star_status star_group_update(float *params, float *momentum, const void *const 
                               const star_hparams *hp, float *norms_out, void *hip_stream);
 
 /*
+ * star_group_update that also writes a copy of the updated parameters for the
+ * "send the updated parameters to the workers" leg (Section 2): after the U
+ * updates, publish[j] = params[j] converted to publish_dtype (fp32: the same
+ * bits; bf16: round to nearest even), written in the same pass, so the send
+ * buffer costs no extra read of params.
+ *   publish : device, P elements of publish_dtype; must not alias any other
+ *             buffer of the call.  With U == 0 nothing is written.
+ */
+star_status star_group_update_publish(float *params, float *momentum, const void *const *grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
+                                      const star_hparams *hp, float *norms_out, void *publish,
+                                      star_dtype publish_dtype, void *hip_stream);
+
+/*
  * Per-group gradient norms only: norms_out[u] = || sum_w c_{u,w} g_w ||_2
  * (gradient-norm signal, Sections 4.3.1 and 7).  Arguments as above; wmode is
  * a star_wmode.  No parameter state is read or written.

@@ -58,6 +58,8 @@ def load_library():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.star_group_update.restype = ctypes.c_int
     lib.star_group_update.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp]
+    lib.star_group_update_publish.restype = ctypes.c_int
+    lib.star_group_update_publish.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.star_group_norms.restype = ctypes.c_int
     lib.star_group_norms.argtypes = [vp, ctypes.c_int, i64, i32, vp, i32, vp, vp]
     lib.star_group_reduce.restype = ctypes.c_int
@@ -161,6 +163,28 @@ def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStre
     _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
                                  ctypes.byref(updates.c), ctypes.byref(hp),
                                  None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
+
+
+def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: UpdateStream, publish, *, lr: float,
+                              momentum_coef: float, weight_decay: float = 0.0, wmode="mean",
+                              scale_lr_by_group: bool = False, norms_out=None, stream=None) -> None:
+    """star_group_update that also writes the updated parameters into ``publish``
+    (float32 or bfloat16 CUDA tensor [P]) in the same pass."""
+    import torch
+    lib = load_library()
+    P = int(params.shape[0])
+    if not (params.is_contiguous() and momentum.is_contiguous()) or momentum.shape[0] != P:
+        raise ValueError("params and momentum must be contiguous and of equal length")
+    if publish.shape[0] != P or not publish.is_contiguous() or publish.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("publish must be a contiguous float32 or bfloat16 tensor of the shard's length")
+    ptrs, dt = _rows(grad_rows, P)
+    hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
+    if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
+        raise ValueError("norms_out must hold U floats")
+    _check(lib.star_group_update_publish(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                         ctypes.byref(updates.c), ctypes.byref(hp),
+                                         None if norms_out is None else norms_out.data_ptr(), publish.data_ptr(),
+                                         F32 if publish.dtype == torch.float32 else BF16, _stream_handle(stream)))
 
 
 def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, wmode="mean", stream=None) -> None:

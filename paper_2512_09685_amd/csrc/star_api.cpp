@@ -159,7 +159,7 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
 // The shared body of star_group_update (update = true) and star_group_norms.
 star_status run(bool update, float* params, float* momentum, const void* const* grad_rows, int grad_dtype,
                 int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode,
-                float* norms_out, void* hip_stream) {
+                float* norms_out, void* publish, int publish_dtype, void* hip_stream) {
     g_err.clear();
     if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
     if (update && !hp) return set_err(STAR_ERR_NULL, "hyper-parameter struct is NULL");
@@ -168,6 +168,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
     if (update && P > 0 && (!params || !momentum)) return set_err(STAR_ERR_NULL, "params or momentum is NULL");
     if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
+    if (publish && publish_dtype != STAR_F32 && publish_dtype != STAR_BF16)
+        return set_err(STAR_ERR_DTYPE, "unknown publish dtype");
 
     const bool want_norms = norms_out != nullptr;
     star::Plan plan;
@@ -197,7 +199,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
     // rows in compact order; padding rows repeat the last row with zero coefficients
     star::RowPtrs rows;
-    bool vec_ok = !update || (aligned16(params) && aligned16(momentum));
+    bool vec_ok = !update || (aligned16(params) && aligned16(momentum) && aligned16(publish));
     for (int k = 0; k < STAR_MAX_WORKERS; ++k) {
         rows.p[k] = grad_rows[plan.row_of[std::min(k, Wc - 1)]];
         if (k < Wc && !aligned16(rows.p[k])) vec_ok = false;
@@ -257,6 +259,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             }
             a.P = P;
             a.vec_ok = vec_ok ? 1 : 0;
+            a.publish = update ? publish : nullptr;
+            a.publish_dtype = publish_dtype;
             a.partials = slot->partials;
             e = star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
@@ -289,6 +293,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.wd = (float)plan.wd;
             a.P = P;
             a.vec_ok = vec_ok ? 1 : 0;
+            a.publish = (seq_update && u0 + n == U) ? publish : nullptr;   // the last launch holds the final params
+            a.publish_dtype = publish_dtype;
             a.partials = slot->partials;
             e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");
@@ -393,12 +399,22 @@ extern "C" {
 star_status star_group_update(float* params, float* momentum, const void* const* grad_rows, star_dtype grad_dtype,
                               int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
                               float* norms_out, void* hip_stream) {
-    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, hip_stream);
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, hip_stream);
+}
+
+star_status star_group_update_publish(float* params, float* momentum, const void* const* grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
+                                      const star_hparams* hp, float* norms_out, void* publish,
+                                      star_dtype publish_dtype, void* hip_stream) {
+    if (!publish && P > 0) return set_err(STAR_ERR_NULL, "publish buffer is NULL");
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, publish,
+               (int)publish_dtype, hip_stream);
 }
 
 star_status star_group_norms(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
                              const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
-    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, hip_stream);
+    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, nullptr, 0,
+               hip_stream);
 }
 
 star_status star_group_reduce(void* const* out_rows, star_dtype out_dtype, const void* const* grad_rows,

@@ -59,6 +59,34 @@ __device__ __forceinline__ void store_streaming(f32x4 x, f32x4* dst) {
     __builtin_nontemporal_store(x, dst);
 }
 
+// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return b >> 16;
+}
+
+// Streaming store of 4 consecutive values as fp32 or as bf16 (chunk index c).
+__device__ __forceinline__ void publish_chunk(f32x4 x, void* dst, int as_bf16, int64_t c) {
+    if (as_bf16) {
+        u32x2 packed;
+        packed[0] = bf16_bits_rne(x[0]) | (bf16_bits_rne(x[1]) << 16);
+        packed[1] = bf16_bits_rne(x[2]) | (bf16_bits_rne(x[3]) << 16);
+        asm volatile("" : "+v"(packed));
+        __builtin_nontemporal_store(packed, reinterpret_cast<u32x2*>(dst) + c);
+    } else {
+        store_streaming(x, reinterpret_cast<f32x4*>(dst) + c);
+    }
+}
+
+__device__ __forceinline__ void publish_element(float x, void* dst, int as_bf16, int64_t j) {
+    if (as_bf16)
+        reinterpret_cast<uint16_t*>(dst)[j] = (uint16_t)bf16_bits_rne(x);
+    else
+        reinterpret_cast<float*>(dst)[j] = x;
+}
+
 // ---------------------------------------------------------------- wave64 sum
 // Sum over the 64 lanes with data-parallel-primitive moves; the total lands in
 // lane 63.  Stages: swap within pairs, within quads, mirror within 8, mirror

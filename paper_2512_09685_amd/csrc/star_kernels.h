@@ -40,6 +40,8 @@ struct SeqArgs {
     float mu, wd;
     int64_t P;
     int32_t vec_ok;        // all buffers 16-byte aligned
+    void* publish;         // device copy of the new params (P elements), or null
+    int32_t publish_dtype; // star_dtype of that copy
     double* partials;      // device [U][grid] sums of gbar^2 per block (norms only)
 };
 
@@ -59,6 +61,8 @@ struct AffArgs {
     AffCoef cf;
     int64_t P;
     int32_t vec_ok;
+    void* publish;          // device copy of the new params (P elements), or null
+    int32_t publish_dtype;  // star_dtype of that copy
     double* partials;  // device [Wp(Wp+1)/2][grid] pairwise-product sums per block (gram only)
 };
 

@@ -62,6 +62,7 @@ template <int W, class R, bool UPDATE, bool GRAM>
 __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
+                                                     void* __restrict__ publish, const int publish_bf16,
                                                      double* __restrict__ partials) {
     constexpr int VEC = R::VEC;
     constexpr int NG = W * (W + 1) / 2;
@@ -126,6 +127,7 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
                 f32x4 vq = {ve[4 * q], ve[4 * q + 1], ve[4 * q + 2], ve[4 * q + 3]};
                 store_streaming(pq, reinterpret_cast<f32x4*>(params) + c * (VEC / 4) + q);
                 store_streaming(vq, reinterpret_cast<f32x4*>(momentum) + c * (VEC / 4) + q);
+                if (publish) publish_chunk(pq, publish, publish_bf16, c * (VEC / 4) + q);
             }
         }
     }
@@ -143,6 +145,7 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
             aff_step<W>(pe, ve, ge, cf);
             params[j] = pe;
             momentum[j] = ve;
+            if (publish) publish_element(pe, publish, publish_bf16, j);
         }
         if constexpr (GRAM) gram_step<W>(acc, ge);
     }
@@ -207,6 +210,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const uint32_t* __restrict__ t_mask, const int U,
                                                      const float mu, const float wd, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
+                                                     void* __restrict__ publish, const int publish_bf16,
                                                      double* __restrict__ partials) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
     extern __shared__ float lds[];
@@ -260,6 +264,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
             }
             store_streaming(pv, reinterpret_cast<f32x4*>(params) + c);
             store_streaming(vv, reinterpret_cast<f32x4*>(momentum) + c);
+            if (publish) publish_chunk(pv, publish, publish_bf16, c);
         }
     }
     const int64_t nrest = P - nchunk * 4;
@@ -281,6 +286,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
         if constexpr (UPDATE) {
             params[j] = p[0];
             momentum[j] = v[0];
+            if (publish) publish_element(p[0], publish, publish_bf16, j);
         }
     }
 
@@ -373,7 +379,8 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
     const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
-                       a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.partials);
+                       a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,
+                       a.partials);
     return hipGetLastError();
 }
 
@@ -383,7 +390,7 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     const Geometry g = pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
-                       g.span_g, g.span_k, a.partials);
+                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials);
     return hipGetLastError();
 }
 

@@ -13,14 +13,6 @@
 
 namespace star {
 
-// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet bit forced).
-__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
-    uint32_t b = __float_as_uint(x);
-    if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return b >> 16;
-}
-
 // LDS: out pointers [U] (8 bytes each) | coef[U][W] | mask[U] | (norms) wave[4][U] | nacc[U][kBlock]
 template <int W, class R>
 __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows, const float* __restrict__ t_coef,
@@ -87,16 +79,8 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
             });
         });
         walk(g, [&](void* out, const float (&gb)[4]) {
-            if (out_bf16) {
-                u32x2 packed;
-                packed[0] = bf16_bits_rne(gb[0]) | (bf16_bits_rne(gb[1]) << 16);
-                packed[1] = bf16_bits_rne(gb[2]) | (bf16_bits_rne(gb[3]) << 16);
-                asm volatile("" : "+v"(packed));
-                __builtin_nontemporal_store(packed, reinterpret_cast<u32x2*>(out) + c);
-            } else {
-                f32x4 x = {gb[0], gb[1], gb[2], gb[3]};
-                store_streaming(x, reinterpret_cast<f32x4*>(out) + c);
-            }
+            const f32x4 x = {gb[0], gb[1], gb[2], gb[3]};
+            publish_chunk(x, out, out_bf16, c);
         });
     }
     const int64_t nrest = P - nchunk * 4;
@@ -110,10 +94,7 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
             g[w][1] = g[w][2] = g[w][3] = 0.0f;
         }
         walk(g, [&](void* out, const float (&gb)[4]) {
-            if (out_bf16)
-                reinterpret_cast<uint16_t*>(out)[j] = (uint16_t)bf16_bits_rne(gb[0]);
-            else
-                reinterpret_cast<float*>(out)[j] = gb[0];
+            publish_element(gb[0], out, out_bf16, j);
         });
     }
 

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "star.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
-    assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_plan_affine", "star_plan_choice", "star_set_kernel",
+    assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_plan_affine", "star_plan_choice", "star_set_kernel",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
