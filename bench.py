@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per-config table)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine"])
+    ap.add_argument("--op", default="update", choices=["update", "publish", "reduce"],
+                    help="update: star_group_update (the headline path); publish: the same with a bf16 copy of the "
+                         "new params written in the pass; reduce: star_group_reduce, one full-group aggregation per call")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, run three plain device copies of 1 GiB (a known-size kernel to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -62,8 +65,9 @@ def kernel_label(star, wl, us):
     return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa
 
 
-def measure(wl, steps, warmup, torch, star, workloads):
+def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     """Times `steps` steps of workload `wl`; returns a dict of results."""
+    import numpy as np
     dev = "cuda"
     stream = torch.cuda.Stream()
     p = workloads.make_params(wl, 0, dev)
@@ -76,11 +80,27 @@ def measure(wl, steps, warmup, torch, star, workloads):
         streams.append(star.UpdateStream(s["offsets"], s["members"], s["staleness"]))
     norms = [torch.zeros(wl.U, device=dev) for _ in range(wl.calls)] if wl.norms else [None] * wl.calls
     hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    extra_bytes = 0
+    if op == "publish":
+        pub = torch.empty(wl.P, dtype=torch.bfloat16, device=dev)
+        extra_bytes = 2 * wl.P
+    if op == "reduce":
+        # one aggregation of all W rows per call (a parent adding its children's gradients to its own),
+        # output in the gradients' dtype
+        full = star.UpdateStream(np.array([0, wl.W], np.int32), np.arange(wl.W, dtype=np.int32))
+        out = [torch.empty(wl.P, dtype=sets[0][0].dtype, device=dev)]
     torch.cuda.synchronize()
 
     def step():
         for c in range(wl.calls):
-            star.star_group_update(p, v, sets[c % nsets], streams[c], norms_out=norms[c], stream=stream, **hp)
+            if op == "update":
+                star.star_group_update(p, v, sets[c % nsets], streams[c], norms_out=norms[c], stream=stream, **hp)
+            elif op == "publish":
+                star.star_group_update_publish(p, v, sets[c % nsets], streams[c], pub, norms_out=norms[c],
+                                               stream=stream, **hp)
+            else:
+                star.star_group_reduce(out, sets[c % nsets], full, norms_out=None if norms[c] is None else norms[c][:1],
+                                       stream=stream)
 
     for _ in range(warmup):
         step()
@@ -102,14 +122,20 @@ def measure(wl, steps, warmup, torch, star, workloads):
     used = set()
     for us in streams:
         used |= set(int(x) for x in us.members)
-    bytes_per_call = wl.algorithmic_bytes_per_call(len(used))
+    bytes_per_call = wl.algorithmic_bytes_per_call(len(used)) + extra_bytes
+    n_updates = wl.U
+    label, fs, fa = kernel_label(star, wl, streams[0])
+    if op == "reduce":
+        bytes_per_call = wl.P * (wl.W * wl.grad_bytes + wl.grad_bytes)      # W rows read, one output row written
+        n_updates = 1
+        label = f"reduce_rows_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>"
+        fs, fa = float(wl.W + (1 if wl.norms else 0)), None
     bytes_per_step = bytes_per_call * wl.calls
     gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
-    label, fs, fa = kernel_label(star, wl, streams[0])
     res = {
-        "workload": wl.name, "P": wl.P, "W": wl.W, "U_per_call": wl.U, "calls_per_step": wl.calls,
+        "workload": wl.name, "op": op, "P": wl.P, "W": wl.W, "U_per_call": wl.U, "calls_per_step": wl.calls,
         "grad_dtype": wl.grad_dtype, "norms": wl.norms,
-        "group_updates_per_s": wl.U * wl.calls / (ms_per_step * 1e-3),
+        "group_updates_per_s": n_updates * wl.calls / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms / steps,
         "algorithmic_bytes_per_step": bytes_per_step, "bytes_per_element": bytes_per_call / wl.P,
         "hbm_gbps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "kernel": label,
@@ -117,6 +143,10 @@ def measure(wl, steps, warmup, torch, star, workloads):
         "launch_ms": ms_per_step / wl.calls, "bytes_per_launch": bytes_per_call,
     }
     del p, v, sets, norms
+    if op == "publish":
+        del pub
+    if op == "reduce":
+        del out
     torch.cuda.empty_cache()
     return res
 
@@ -180,7 +210,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    head = measure(head_wl, a.steps, a.warmup, torch, star, workloads)
+    head = measure(head_wl, a.steps, a.warmup, torch, star, workloads, a.op)
     per_config = []
     if not a.only:
         for name in workloads.ORDER:
@@ -188,23 +218,23 @@ def main():
                 per_config.append(head)
             else:
                 per_config.append(measure(workloads.WORKLOADS[name], max(3, min(a.steps, 10)), min(a.warmup, 2),
-                                          torch, star, workloads))
+                                          torch, star, workloads, a.op))
     out = {
-        "metric": "group_updates_per_s",
+        "metric": "group_updates_per_s" if a.op != "reduce" else "group_aggregations_per_s",
         "value": head["group_updates_per_s"],
         "unit": "group-updates/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": a.workload, "P": head_wl.P, "W": head_wl.W, "U": head_wl.U * head_wl.calls,
+        "config": {"workload": a.workload, "op": a.op, "P": head_wl.P, "W": head_wl.W, "U": head_wl.U * head_wl.calls,
                    "grad_dtype": head_wl.grad_dtype, "norms": head_wl.norms, "kernel_choice": a.kernel},
         "hbm_gbps": head["hbm_gbps"],
         "roofline": {
             "bound": "hbm", "achieved": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "traffic": measured_traffic(a.workload), "kernel": head["kernel"],
+            "traffic": measured_traffic(a.workload) if a.op == "update" else None, "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "
                     "norm-finishing kernels that follow each update kernel",

@@ -146,12 +146,18 @@ struct Geometry {
 // the set of addresses in flight a narrow window that advances through every
 // row together, which is what measured fastest on MI355X for this mix of 16+
 // read streams and two read-modify-write streams.
-inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int num_cu, int grid_cap) {
+// `thread_bytes`: bytes one thread has in flight per tile; long-lived workgroups are stacked on a compute unit
+// (up to `max_per_cu`) until about 64 KB per unit are in flight, which light bf16 kernels need and heavy fp32
+// ones already have with one workgroup.
+inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int num_cu, int grid_cap,
+                              int thread_bytes = 256, int max_per_cu = 1) {
     const int64_t items = vec_ok ? std::max<int64_t>(P / vec, P % vec) : P;
     const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
     Geometry g;
     if (reduces) {
-        g.span_g = (int)std::min<int64_t>(std::min(num_cu, grid_cap), tiles);
+        const int wg_bytes = std::max(1, thread_bytes) * kBlock;
+        const int bpc = std::max(1, std::min(max_per_cu, (64 * 1024 + wg_bytes - 1) / wg_bytes));
+        g.span_g = (int)std::min<int64_t>(std::min(num_cu * bpc, grid_cap), tiles);
         g.span_k = 0x7fffffff;
         g.grid = g.span_g;
     } else {

@@ -376,7 +376,8 @@ template <int W, class R, bool UPDATE, bool NORMS>
 hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = seq_kernel<W, R, UPDATE, NORMS>;
     const size_t lds = seq_lds_bytes(W, a.U, NORMS);
-    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap);
+    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap,
+                                     W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0), 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
                        a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,

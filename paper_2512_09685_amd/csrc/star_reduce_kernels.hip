@@ -125,7 +125,8 @@ template <int W, class R>
 hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = reduce_rows_kernel<W, R>;
     const size_t lds = reduce_lds_bytes(W, a.U, a.norms != 0);
-    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap);
+    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
+                                     W * (int)sizeof(typename R::vec), 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.rows, a.coef, a.mask, a.out, a.U,
                        a.out_dtype == STAR_BF16 ? 1 : 0, a.P, a.vec_ok, a.norms, g.span_g, g.span_k, a.partials);
