@@ -182,6 +182,70 @@ star_status star_plan_affine(int32_t W, const star_updates *upd, const star_hpar
 star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hparams *hp, int32_t want_norms,
                              int32_t *kernel_out, double *fma_seq, double *fma_affine);
 
+/* ---- STAR-H: heuristic choice of the synchronization mode (host only) ---- */
+
+typedef enum {
+    STAR_MODE_SSGD = 0,      /* every update uses all N workers                    */
+    STAR_MODE_ASGD = 1,      /* every update uses one worker                       */
+    STAR_MODE_STATIC_X = 2,  /* every update uses x workers, 1 < x < N             */
+    STAR_MODE_DYNAMIC_X = 3  /* one update per cluster of workers of similar speed */
+} star_mode;
+
+typedef struct {
+    int32_t mode;            /* star_mode                                                    */
+    int32_t x;               /* workers per update of the static modes (N: SSGD, 1: ASGD); 0 for dynamic */
+    int32_t n_groups;        /* groups written to group_offsets / group_members              */
+    int32_t n_stragglers;    /* workers with d_i above the straggler threshold               */
+    int32_t n_clusters;      /* clusters the dynamic mode would use                          */
+    double time_to_progress; /* T of the chosen mode                                         */
+} star_mode_choice;
+
+/*
+ * Parameter-server architecture (Section 4.3.1).  From the predicted iteration
+ * times of the N workers, the noise scale phi of the current step and the
+ * total batch size M:  T_x = (1 + phi/(x M/N)) t_x for x = 1..N (Eq. 1),
+ * T_d = 1 / sum_i 1/((1 + phi/(n_ci M/N)) t_ci) over the clusters of workers
+ * with similar times (Eq. 2), and the mode with the least time.  A worker is a
+ * straggler when (T_i - min T)/min T > straggler_threshold (Section 2; the
+ * paper uses 0.2); without any straggler the choice is SSGD.
+ * t_x is taken as the x-th smallest iteration time (the time by which x
+ * gradient reports have arrived); clusters come from
+ * complete-linkage agglomerative clustering that merges while the merged
+ * range relative to its fastest member is within cluster_threshold.
+ *   iter_time     : host double[N], predicted iteration times (> 0)
+ *   choice        : host, result
+ *   time_static   : host double[N] or NULL, receives T_x at [x-1]
+ *   time_dynamic  : host double* or NULL, receives T_d
+ *   group_offsets : host int32[N+1], group_members : host int32[N]: the groups
+ *                   of the chosen mode, fastest group first, in the format of
+ *                   star_updates (use scale_lr_by_group for the rate rule).
+ *   is_straggler  : host int32[N] or NULL.
+ * Errors: STAR_ERR_NULL, STAR_ERR_SHAPE (N outside [1, STAR_MAX_WORKERS]),
+ * STAR_ERR_HPARAM (non-positive or non-finite times, batch, thresholds, phi < 0).
+ */
+star_status star_select_mode_ps(int32_t N, const double *iter_time, double phi, double batch_total,
+                                double straggler_threshold, double cluster_threshold, star_mode_choice *choice,
+                                double *time_static, double *time_dynamic, int32_t *group_offsets,
+                                int32_t *group_members, int32_t *is_straggler);
+
+/*
+ * All-reduce architecture (Section 4.3.1, Eq. 3): remove the x slowest
+ * workers (x at most the number of stragglers) from the ring, let parents wait
+ * t_w, and minimise T_a = (1 + phi/((N-x+q) M/N)) (t_ring + t_w) over x and the
+ * candidate waits; t_ring is the slowest remaining ring worker, q the removed
+ * workers whose new iteration time child_time[k] is no higher than t_w.
+ * x = 0 (the plain ring, no wait) is always a candidate.
+ *   child_time      : host double[N], iteration time of worker k if removed
+ *   wait_candidates : host double[n_wait]
+ *   removed_out, wait_out, time_out : chosen x, t_w and T_a
+ *   time_table      : host double[1 + X*n_wait] or NULL: T_a of the plain ring,
+ *                     then of (x, wait index) row by row, X = stragglers.
+ */
+star_status star_select_mode_ar(int32_t N, const double *iter_time, const double *child_time, double phi,
+                                double batch_total, double straggler_threshold, int32_t n_wait,
+                                const double *wait_candidates, int32_t *removed_out, double *wait_out,
+                                double *time_out, double *time_table);
+
 /* Force an evaluation for later calls of this process (default AUTO; the
  * environment variable STAR_KERNEL=auto|seq|affine sets the initial value). */
 star_status star_set_kernel(int32_t kernel);

@@ -239,6 +239,63 @@ def star_plan_choice(W: int, updates: UpdateStream, *, lr: float, momentum_coef:
     return k.value, a.value, b.value
 
 
+class _ModeChoice(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("x", ctypes.c_int32), ("n_groups", ctypes.c_int32),
+                ("n_stragglers", ctypes.c_int32), ("n_clusters", ctypes.c_int32),
+                ("time_to_progress", ctypes.c_double)]
+
+
+MODE_SSGD, MODE_ASGD, MODE_STATIC_X, MODE_DYNAMIC_X = 0, 1, 2, 3
+
+
+def star_select_mode_ps(iter_time, phi: float, batch_total: float, *, straggler_threshold: float = 0.2,
+                        cluster_threshold: float = 0.2):
+    """Host-only STAR-H for the parameter-server architecture.  Returns a dict:
+    mode, x, time_to_progress, n_stragglers, n_clusters, time_static [N], time_dynamic,
+    groups (list of lists of worker ids, fastest first), is_straggler [N]."""
+    lib = load_library()
+    t = np.ascontiguousarray(iter_time, dtype=np.float64)
+    N = int(t.shape[0])
+    ch = _ModeChoice()
+    ts = np.zeros(max(N, 1), dtype=np.float64)
+    td = ctypes.c_double(0)
+    offs = np.zeros(N + 1, dtype=np.int32)
+    mem = np.zeros(max(N, 1), dtype=np.int32)
+    strag = np.zeros(max(N, 1), dtype=np.int32)
+    lib.star_select_mode_ps.restype = ctypes.c_int
+    st = lib.star_select_mode_ps(ctypes.c_int32(N), _np_ptr(t), ctypes.c_double(phi), ctypes.c_double(batch_total),
+                                 ctypes.c_double(straggler_threshold), ctypes.c_double(cluster_threshold),
+                                 ctypes.byref(ch), _np_ptr(ts), ctypes.byref(td), _np_ptr(offs), _np_ptr(mem),
+                                 _np_ptr(strag))
+    if st != 0:
+        raise StarError(st, "star_select_mode_ps rejected its arguments")
+    groups = [mem[offs[g]:offs[g + 1]].tolist() for g in range(ch.n_groups)]
+    return {"mode": ch.mode, "x": ch.x, "time_to_progress": ch.time_to_progress, "n_stragglers": ch.n_stragglers,
+            "n_clusters": ch.n_clusters, "time_static": ts[:N].copy(), "time_dynamic": td.value, "groups": groups,
+            "offsets": offs[:ch.n_groups + 1].copy(), "members": mem[:N].copy(),
+            "is_straggler": strag[:N].astype(bool)}
+
+
+def star_select_mode_ar(iter_time, child_time, phi: float, batch_total: float, wait_candidates, *,
+                        straggler_threshold: float = 0.2):
+    """Host-only STAR-H for the all-reduce architecture: (removed x, wait t_w, T_a, table)."""
+    lib = load_library()
+    t = np.ascontiguousarray(iter_time, dtype=np.float64)
+    c = np.ascontiguousarray(child_time, dtype=np.float64)
+    w = np.ascontiguousarray(wait_candidates, dtype=np.float64)
+    N, nw = int(t.shape[0]), int(w.shape[0])
+    x, tw, ta = ctypes.c_int32(0), ctypes.c_double(0), ctypes.c_double(0)
+    table = np.full(1 + N * max(nw, 1), np.nan, dtype=np.float64)
+    lib.star_select_mode_ar.restype = ctypes.c_int
+    st = lib.star_select_mode_ar(ctypes.c_int32(N), _np_ptr(t), _np_ptr(c), ctypes.c_double(phi),
+                                 ctypes.c_double(batch_total), ctypes.c_double(straggler_threshold),
+                                 ctypes.c_int32(nw), _np_ptr(w) if nw else None, ctypes.byref(x), ctypes.byref(tw),
+                                 ctypes.byref(ta), _np_ptr(table))
+    if st != 0:
+        raise StarError(st, "star_select_mode_ar rejected its arguments")
+    return x.value, tw.value, ta.value, table
+
+
 def star_set_kernel(kernel: int) -> None:
     _check(load_library().star_set_kernel(kernel))
 

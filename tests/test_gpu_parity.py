@@ -266,3 +266,21 @@ def test_non_default_stream_and_back_to_back_calls():
         ep, ev, en = so.group_update(ep, ev, sets[call][0], offs, mem, staleness=st, want_norms=True, **hp)
         np.testing.assert_allclose(norms[call].cpu().numpy(), en, rtol=TOL["bf16"])
     check(p.cpu().numpy(), v.cpu().numpy(), None, ep, ev, None, "bf16", "4 streamed calls")
+
+
+def test_selector_groups_drive_the_update():
+    """Iteration times -> STAR-H groups (dynamic x-order here) -> one round of
+    updates with the rate scaled by the group size, against the oracle."""
+    rng = np.random.default_rng(14)
+    T = [0.30, 0.31, 0.33, 0.52, 0.55, 0.90, 0.29, 0.32]
+    r = star.star_select_mode_ps(T, 4000.0, 1024.0)
+    assert r["mode"] == star.MODE_DYNAMIC_X and len(r["groups"]) == 3
+    W, P = len(T), 30011
+    rows = rand_rows(rng, W, P, "f32")
+    p0 = rng.standard_normal(P).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=0.1, momentum_coef=0.9, weight_decay=1e-4, scale_lr_by_group=True, want_norms=True)
+    ep, ev, en = so.group_update(p0, v0, rows, r["offsets"], r["members"], **hp)
+    for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+        p, v, n = gpu_update(p0, v0, rows, r["offsets"], r["members"], kernel=kern, **hp)
+        check(p, v, n, ep, ev, en, "f32", f"selector kern={kern}")
