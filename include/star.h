@@ -182,6 +182,35 @@ star_status star_plan_affine(int32_t W, const star_updates *upd, const star_hpar
 star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hparams *hp, int32_t want_norms,
                              int32_t *kernel_out, double *fma_seq, double *fma_affine);
 
+/*
+ * Gram matrix of the gradient rows, Gamma[a][b] = sum_j g_a[j] g_b[j], the
+ * quantity the per-group norms are derived from (|| sum_w c_w g_w ||^2 =
+ * c^T Gamma c) and the input of the noise-scale estimate below.
+ *   grad_rows : host array of W device pointers, all used; 1 <= W <= 16
+ *   gram_out  : device double[W*W], row-major, symmetric
+ * One pass over the rows; products and per-thread sums in fp32, across
+ * workgroups in fp64.
+ */
+star_status star_group_gram(const void *const *grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                            double *gram_out, void *hip_stream);
+
+/*
+ * Host-only: gradient noise scale from the Gram matrix of W workers' gradients
+ * of one step (the gradient-norm progress signal the paper lists as future
+ * work, Section 7; the simple noise scale tr(Sigma)/|G|^2, i.e. the PGNS of
+ * Section 4.3.1 with the identity as pre-conditioner).  Model: g_w = G + e_w,
+ * e_w independent, zero mean, covariance Sigma / batch_per_worker.  Then
+ *   E mean_w |g_w|^2 = |G|^2 + tr(Sigma)/b,   E |mean_w g_w|^2 = |G|^2 + tr(Sigma)/(W b),
+ * and solving the two for the unknowns gives the unbiased estimates
+ *   trace_cov = b (S - n2) W/(W-1),  grad_sq = (W n2 - S)/(W-1),  noise_scale = trace_cov / grad_sq,
+ * S = mean of the diagonal of Gamma, n2 = sum of all entries of Gamma / W^2.
+ *   gram : host double[W*W] (copy of star_group_gram's output); 2 <= W <= 32.
+ * Any of the three outputs may be NULL.  grad_sq can come out negative when
+ * the noise dominates; noise_scale is then negative or huge and means "unknown".
+ */
+star_status star_noise_scale(int32_t W, const double *gram, double batch_per_worker, double *grad_sq,
+                             double *trace_cov, double *noise_scale);
+
 /* ---- STAR-H: heuristic choice of the synchronization mode (host only) ---- */
 
 typedef enum {

@@ -209,6 +209,24 @@ int oracle_group_reduce(double *out, const void *const *rows, int grad_dtype, in
 }
 
 /*
+ * Gram matrix of the gradient rows: out[a*W + b] = sum_j g_a[j] g_b[j].  The
+ * squared norm of any weighted sum of rows is the quadratic form of its
+ * coefficients in this matrix; it also feeds the noise-scale estimate (the
+ * gradient-norm signal of Sections 4.3.1 and 7).
+ */
+int oracle_gram(double *out, const void *const *rows, int grad_dtype, int64_t P, int32_t W)
+{
+    for (int32_t a = 0; a < W; ++a)
+        for (int32_t b = 0; b < W; ++b) {
+            double s = 0.0;
+            for (int64_t j = 0; j < P; ++j)
+                s += grad_at(rows[a], grad_dtype, j) * grad_at(rows[b], grad_dtype, j);
+            out[(int64_t)a * W + b] = s;
+        }
+    return 0;
+}
+
+/*
  * Stepwise-fp32 mode: what a literal fp32 parameter server produces.  Every
  * product and sum is rounded to fp32 (this file is compiled with
  * -ffp-contract=off, so no fused multiply-add), members are taken in

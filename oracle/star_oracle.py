@@ -53,7 +53,7 @@ def _load():
         # broken build of the oracle (on the CPU) to show that the pins catch it.
         _lib = ctypes.CDLL(os.environ.get("STAR_ORACLE_LIB") or build())
         for name in ("oracle_group_update", "oracle_group_update_f64", "oracle_group_update_f32step",
-                     "oracle_group_norms", "oracle_group_reduce"):
+                     "oracle_group_norms", "oracle_group_reduce", "oracle_gram"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -157,6 +157,29 @@ def group_reduce(rows: Sequence[np.ndarray], offsets, members, *, wmode: str = "
     if rc:
         raise ValueError(f"oracle rejected the update stream (code {rc})")
     return (out, norms) if want_norms else out
+
+
+def gram(rows: Sequence[np.ndarray]) -> np.ndarray:
+    """Gram matrix of the rows, float64 [W, W]."""
+    lib = _load()
+    m = _Marshal(rows, [0], [], None, None, None)
+    out = np.zeros((m.W, m.W), dtype=np.float64)
+    lib.oracle_gram(_ptr(out), m.rowptr, m.dtype, ctypes.c_int64(m.P), m.W)
+    return out
+
+
+def noise_scale(rows: Sequence[np.ndarray], batch_per_worker: float):
+    """(grad_sq, trace_cov, noise_scale) straight from the rows, from the model
+    g_w = G + e_w, Cov e_w = Sigma / b:  E mean|g_w|^2 = |G|^2 + tr/b and
+    E |mean g_w|^2 = |G|^2 + tr/(W b), solved for |G|^2 and tr(Sigma)."""
+    R = np.stack([np.asarray(r, dtype=np.float64) for r in rows])
+    W = R.shape[0]
+    S = float(np.mean(np.sum(R * R, axis=1)))
+    gbar = R.mean(axis=0)
+    n2 = float(gbar @ gbar)
+    tr = batch_per_worker * (S - n2) * W / (W - 1)
+    g2 = (W * n2 - S) / (W - 1)
+    return g2, tr, tr / g2
 
 
 def max_rel_err(x: np.ndarray, ref: np.ndarray) -> float:

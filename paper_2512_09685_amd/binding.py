@@ -239,6 +239,31 @@ def star_plan_choice(W: int, updates: UpdateStream, *, lr: float, momentum_coef:
     return k.value, a.value, b.value
 
 
+def star_group_gram(grad_rows: Sequence, gram_out, *, stream=None) -> None:
+    """gram_out (float64 CUDA tensor [W, W]) = Gram matrix of the W gradient rows."""
+    lib = load_library()
+    P = int(grad_rows[0].shape[0])
+    ptrs, dt = _rows(grad_rows, P)
+    W = len(grad_rows)
+    if gram_out.numel() != W * W or not gram_out.is_contiguous() or gram_out.element_size() != 8:
+        raise ValueError("gram_out must be a contiguous float64 tensor of W*W elements")
+    lib.star_group_gram.restype = ctypes.c_int
+    _check(lib.star_group_gram(ptrs, ctypes.c_int(dt), ctypes.c_int64(P), ctypes.c_int32(W),
+                               ctypes.c_void_p(gram_out.data_ptr()), _stream_handle(stream)))
+
+
+def star_noise_scale(gram, batch_per_worker: float):
+    """Host-only: (grad_sq, trace_cov, noise_scale) from a W x W Gram matrix (numpy float64)."""
+    lib = load_library()
+    g = np.ascontiguousarray(gram, dtype=np.float64)
+    W = int(g.shape[0])
+    a, b, c = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    lib.star_noise_scale.restype = ctypes.c_int
+    _check(lib.star_noise_scale(ctypes.c_int32(W), _np_ptr(g), ctypes.c_double(batch_per_worker), ctypes.byref(a),
+                                ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
+
+
 class _ModeChoice(ctypes.Structure):
     _fields_ = [("mode", ctypes.c_int32), ("x", ctypes.c_int32), ("n_groups", ctypes.c_int32),
                 ("n_stragglers", ctypes.c_int32), ("n_clusters", ctypes.c_int32),

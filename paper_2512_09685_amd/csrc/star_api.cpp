@@ -423,6 +423,73 @@ star_status star_group_reduce(void* const* out_rows, star_dtype out_dtype, const
     return run_reduce(out_rows, (int)out_dtype, grad_rows, (int)grad_dtype, P, W, upd, wmode, norms_out, hip_stream);
 }
 
+star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                            double* gram_out, void* hip_stream) {
+    g_err.clear();
+    if (!grad_rows || !gram_out) return set_err(STAR_ERR_NULL, "grad_rows or gram_out is NULL");
+    if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
+    if (W < 1 || W > star::kMaxGramW) return set_err(STAR_ERR_SHAPE, "the Gram matrix is built for 1 to 16 rows");
+    if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (P == 0) {
+        hipError_t e0 = star::launch_gram_unpack(nullptr, W, gram_out, stream);
+        return e0 == hipSuccess ? STAR_OK : hip_fail(e0, "launch of the Gram unpack kernel");
+    }
+    star::AffArgs a;
+    std::memset(&a, 0, sizeof a);
+    bool vec_ok = true;
+    for (int k = 0; k < STAR_MAX_WORKERS; ++k) {
+        a.rows.p[k] = grad_rows[std::min(k, W - 1)];
+        if (k < W && !a.rows.p[k]) return set_err(STAR_ERR_NULL, "a gradient row is NULL");
+        if (k < W && !aligned16(a.rows.p[k])) vec_ok = false;
+    }
+    int device = 0, num_cu = 1;
+    star_status st = device_info(&device, &num_cu);
+    if (st != STAR_OK) return st;
+    std::lock_guard<std::mutex> lock(g_mu);
+    Slot* slot = nullptr;
+    st = acquire_slot(device, 0, partial_doubles_needed(W, 1, star::kGridCap), &slot);
+    if (st != STAR_OK) return st;
+    a.P = P;
+    a.vec_ok = vec_ok ? 1 : 0;
+    a.partials = slot->partials;
+    int grid = 0;
+    hipError_t e = star::launch_affine(W, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
+    if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");
+    const int ng = W * (W + 1) / 2;
+    double* gamma = slot->partials + (size_t)ng * grid;
+    e = star::launch_reduce(slot->partials, ng, grid, gamma, nullptr, stream);
+    if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
+    e = star::launch_gram_unpack(gamma, W, gram_out, stream);
+    if (e != hipSuccess) return hip_fail(e, "launch of the Gram unpack kernel");
+    STAR_HIP(hipEventRecord(slot->done, stream));
+    return STAR_OK;
+}
+
+star_status star_noise_scale(int32_t W, const double* gram, double batch_per_worker, double* grad_sq,
+                             double* trace_cov, double* noise_scale) {
+    g_err.clear();
+    if (!gram) return set_err(STAR_ERR_NULL, "gram is NULL");
+    if (W < 2 || W > STAR_MAX_WORKERS) return set_err(STAR_ERR_SHAPE, "needs between 2 and 32 workers");
+    if (!(batch_per_worker > 0.0) || !std::isfinite(batch_per_worker))
+        return set_err(STAR_ERR_HPARAM, "batch size per worker must be positive");
+    // S = mean_w |g_w|^2 ;  n2 = |mean_w g_w|^2 = (1/W^2) sum_ab Gamma_ab
+    double S = 0.0, total = 0.0;
+    for (int a = 0; a < W; ++a) {
+        S += gram[(size_t)a * W + a];
+        for (int b = 0; b < W; ++b) total += gram[(size_t)a * W + b];
+    }
+    S /= W;
+    const double n2 = total / ((double)W * W);
+    // E S = |G|^2 + tr/b,  E n2 = |G|^2 + tr/(W b)   ->   two unbiased estimates
+    const double tr = batch_per_worker * (S - n2) * W / (W - 1.0);
+    const double g2 = (W * n2 - S) / (W - 1.0);
+    if (grad_sq) *grad_sq = g2;
+    if (trace_cov) *trace_cov = tr;
+    if (noise_scale) *noise_scale = tr / g2;
+    return STAR_OK;
+}
+
 star_status star_plan_affine(int32_t W, const star_updates* upd, const star_hparams* hp, double M[4], double* B) {
     g_err.clear();
     if (!hp || !M || !B) return set_err(STAR_ERR_NULL, "hp, M or B is NULL");

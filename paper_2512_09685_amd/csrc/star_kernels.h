@@ -79,6 +79,9 @@ hipError_t launch_reduce(const double* partials, int n_out, int grid, double* su
 hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int Wp, float* norms_out,
                              hipStream_t s);
 
+// Packed upper triangle [W(W+1)/2] -> full symmetric [W][W] (all zero when gamma is null).
+hipError_t launch_gram_unpack(const double* gamma, int W, double* out, hipStream_t s);
+
 hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
 
 // ---- aggregation without the optimizer step (star_group_reduce)

@@ -355,6 +355,17 @@ __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __rest
     if (threadIdx.x == 0 && u < U) norms_out[u] = (float)sqrt(s_part[0] > 0.0 ? s_part[0] : 0.0);
 }
 
+// Packed upper triangle (row-major, a <= b) -> full symmetric W x W matrix; a zero
+// matrix when gamma is null (empty shard).
+__global__ __launch_bounds__(kBlock) void gram_unpack_kernel(const double* __restrict__ gamma, const int W,
+                                                             double* __restrict__ out) {
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= W * W) return;
+    const int r = i / W, c = i % W;
+    const int a = r < c ? r : c, b = r < c ? c : r;
+    out[i] = gamma ? gamma[a * W - a * (a - 1) / 2 + (b - a)] : 0.0;
+}
+
 __global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, const int64_t n, const float value) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < n) dst[i] = value;
@@ -471,6 +482,11 @@ hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int
     if (U < 1) return hipSuccess;
     hipLaunchKernelGGL(gram_norms_kernel, dim3(U), dim3(kBlock), 0, s, gamma, coef, U, Wp,
                        norms_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_unpack(const double* gamma, int W, double* out, hipStream_t s) {
+    hipLaunchKernelGGL(gram_unpack_kernel, dim3((W * W + kBlock - 1) / kBlock), dim3(kBlock), 0, s, gamma, W, out);
     return hipGetLastError();
 }
 

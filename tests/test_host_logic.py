@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "star.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
-    assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_plan_affine", "star_plan_choice", "star_set_kernel",
+    assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_group_gram",
+            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_set_kernel",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
@@ -146,3 +147,18 @@ def test_group_reduce_argument_checks():
     assert call(outs, 0, ptrs, 0, 8, 1) == 3          # member id 1 outside [0, 1)
     assert call((ctypes.c_void_p * 1)(None), 0, ptrs, 0, 8, 4) == 1
     assert call(outs, 0, ptrs, 0, 0, 4) == 0          # empty shard: nothing to do
+
+
+def test_noise_scale_host_function():
+    g2, tr, phi = star.star_noise_scale(np.array([[9.0, 3.0], [3.0, 1.0]]), 8.0)      # rows (3) and (1)
+    assert (g2, tr, phi) == (3.0, 16.0, 16.0 / 3.0)
+    lib = star.load_library()
+    lib.star_noise_scale.restype = ctypes.c_int
+    g = (ctypes.c_double * 4)(9.0, 3.0, 3.0, 1.0)
+    assert lib.star_noise_scale(ctypes.c_int32(1), g, ctypes.c_double(8.0), None, None, None) == 2
+    assert lib.star_noise_scale(ctypes.c_int32(2), None, ctypes.c_double(8.0), None, None, None) == 1
+    assert lib.star_noise_scale(ctypes.c_int32(2), g, ctypes.c_double(0.0), None, None, None) == 4
+    lib.star_group_gram.restype = ctypes.c_int
+    ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
+    assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(17), ctypes.c_void_p(0x9000), None) == 2
+    assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(4), None, None) == 1

@@ -486,3 +486,34 @@ def test_reduce_bf16_rows_and_full_group_mean():
     bits = [np.array([0x3F00, 0x4000], np.uint16), np.array([0xBE80, 0x3F80], np.uint16)]   # 0.5, 2 | -0.25, 1
     out = so.group_reduce(bits, [0, 2], [0, 1])
     assert out[0].tolist() == [0.125, 1.5]
+
+
+# ---------------------------------------------------------------- Gram matrix and noise scale
+def test_gram_matches_matrix_product_and_norm_identity():
+    rng, rows, offs, mem, st, p0, v0 = _setup(23, W=6, P=301, U=5, stale=3)
+    G = so.gram(rows)
+    R = np.stack(rows).astype(np.float64)
+    np.testing.assert_allclose(G, R @ R.T, rtol=1e-13)
+    assert np.array_equal(G, G.T)
+    # || sum_w c_w g_w ||^2 = c^T Gamma c for every group of a stream
+    n = so.group_norms(rows, offs, mem, wmode="stale", staleness=st)
+    for u in range(len(offs) - 1):
+        c = np.zeros(6)
+        ids = mem[offs[u]:offs[u + 1]]
+        c[ids] = 1.0 / (1.0 + st[offs[u]:offs[u + 1]]) / len(ids)
+        np.testing.assert_allclose(n[u] ** 2, c @ G @ c, rtol=1e-12)
+    bits = [np.array([0x3F00, 0x4000], np.uint16), np.array([0xBE80, 0x3F80], np.uint16)]   # (0.5, 2), (-0.25, 1)
+    assert so.gram(bits).tolist() == [[4.25, 1.875], [1.875, 1.0625]]
+
+
+def test_noise_scale_hand_case_and_recovery():
+    # two workers, one element: g = 3 and 1: S = 5, |gbar|^2 = 4 -> tr = b*(5-4)*2 = 2b, |G|^2 = 2*4 - 5 = 3
+    g2, tr, phi = so.noise_scale([f32([3.0]), f32([1.0])], 8.0)
+    assert (g2, tr, phi) == (3.0, 16.0, 16.0 / 3.0)
+    # synthetic gradients with known mean and per-sample covariance sigma^2 I
+    rng = np.random.default_rng(0)
+    W, P, b, sigma = 16, 20000, 32.0, 0.5
+    G = rng.standard_normal(P) * 0.05
+    rows = [(G + rng.standard_normal(P) * sigma / np.sqrt(b)).astype(np.float32) for _ in range(W)]
+    g2, tr, phi = so.noise_scale(rows, b)
+    assert abs(tr / (P * sigma ** 2) - 1) < 0.03 and abs(g2 / float(G @ G) - 1) < 0.1
