@@ -211,7 +211,17 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     st = acquire_slot(device, lay.total, want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
     if (st != STAR_OK) return st;
 
-    const bool need_seq_tables = route != star::Route::Affine;
+    // tables of the step-by-step kernel: in the kernel arguments when small, else staged through the slot
+    const bool seq_inline = route != star::Route::Affine && star::tables_fit_inline(U, Wp);
+    star::InlineTables inl;
+    if (seq_inline) {
+        for (int u = 0; u < U; ++u) {
+            for (int k = 0; k < Wp; ++k) inl.coef[u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
+            inl.lr[u] = (float)plan.lr[u];
+            inl.mask[u] = plan.mask[u];
+        }
+    }
+    const bool need_seq_tables = route != star::Route::Affine && !seq_inline;
     const bool need_gram_coef = want_norms && route == star::Route::Affine;
     char* h = static_cast<char*>(slot->host);
     char* d = static_cast<char*>(slot->dev);
@@ -285,9 +295,10 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.params = params;
             a.momentum = momentum;
             a.rows = rows;
-            a.coef = reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
+            a.coef = seq_inline ? nullptr : reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
             a.lr = reinterpret_cast<const float*>(d + lay.lr32) + u0;
             a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
+            a.inl = &inl;
             a.U = n;
             a.mu = (float)plan.mu;
             a.wd = (float)plan.wd;
@@ -357,23 +368,34 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
     if (st != STAR_OK) return st;
     char* h = static_cast<char*>(slot->host);
     char* d = static_cast<char*>(slot->dev);
-    float* c32 = reinterpret_cast<float*>(h + lay.coef32);
-    uint32_t* mk = reinterpret_cast<uint32_t*>(h + lay.mask);
-    void** op = reinterpret_cast<void**>(h + lay.outptr);
-    for (int u = 0; u < U; ++u) {
-        for (int k = 0; k < Wp; ++k) c32[(size_t)u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
-        mk[u] = plan.mask[u];
-        op[u] = out_rows[u];
+    const bool use_inline = star::tables_fit_inline(U, Wp);
+    star::InlineTables inl;
+    if (use_inline) {
+        for (int u = 0; u < U; ++u) {
+            for (int k = 0; k < Wp; ++k) inl.coef[u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
+            inl.mask[u] = plan.mask[u];
+            inl.out[u] = out_rows[u];
+        }
+    } else {
+        float* c32 = reinterpret_cast<float*>(h + lay.coef32);
+        uint32_t* mk = reinterpret_cast<uint32_t*>(h + lay.mask);
+        void** op = reinterpret_cast<void**>(h + lay.outptr);
+        for (int u = 0; u < U; ++u) {
+            for (int k = 0; k < Wp; ++k) c32[(size_t)u * Wp + k] = k < Wc ? (float)plan.coef[(size_t)u * Wc + k] : 0.0f;
+            mk[u] = plan.mask[u];
+            op[u] = out_rows[u];
+        }
+        STAR_HIP(hipMemcpyAsync(d, h, lay.total, hipMemcpyHostToDevice, stream));
     }
-    STAR_HIP(hipMemcpyAsync(d, h, lay.total, hipMemcpyHostToDevice, stream));
     const int umax = star::reduce_max_updates(Wp, want_norms);
     for (int u0 = 0; u0 < U; u0 += umax) {
         const int n = std::min(umax, U - u0);
         star::ReduceArgs a;
         a.rows = rows;
-        a.coef = reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
+        a.coef = use_inline ? nullptr : reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
         a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
         a.out = reinterpret_cast<void* const*>(d + lay.outptr) + u0;
+        a.inl = &inl;
         a.U = n;
         a.out_dtype = out_dtype;
         a.P = P;

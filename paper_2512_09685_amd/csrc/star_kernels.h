@@ -29,13 +29,27 @@ struct AffCoef {
 // padded_rows(Wc) >= Wc rows, the extra ones carrying zero coefficients.
 int padded_rows(int Wc);
 
+// Small group tables travel in the kernel arguments instead of through a
+// host-to-device copy: a call with one or a few updates (the un-queued
+// parameter-server case) is then a single enqueue.
+constexpr int kInlineUpdates = 32;
+constexpr int kInlineCoef = 256;
+struct InlineTables {
+    float coef[kInlineCoef];        // [U][Wp]
+    float lr[kInlineUpdates];
+    uint32_t mask[kInlineUpdates];
+    void* out[kInlineUpdates];      // output rows (aggregation only)
+};
+inline bool tables_fit_inline(int U, int Wp) { return U <= kInlineUpdates && U * Wp <= kInlineCoef; }
+
 struct SeqArgs {
     float* params;
     float* momentum;
     RowPtrs rows;
-    const float* coef;     // device [U][Wp]
+    const float* coef;     // device [U][Wp], or null: the tables are in `inl`
     const float* lr;       // device [U]
     const uint32_t* mask;  // device [U]
+    const InlineTables* inl;  // host; used when coef is null
     int32_t U;             // updates in this launch
     float mu, wd;
     int64_t P;
@@ -87,9 +101,10 @@ hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
 // ---- aggregation without the optimizer step (star_group_reduce)
 struct ReduceArgs {
     RowPtrs rows;
-    const float* coef;       // device [U][Wp]
+    const float* coef;       // device [U][Wp], or null: the tables are in `inl`
     const uint32_t* mask;    // device [U]
     void* const* out;        // device array of U output row pointers
+    const InlineTables* inl; // host; used when coef is null
     int32_t U;               // groups in this launch
     int32_t out_dtype;       // star_dtype of the outputs
     int64_t P;

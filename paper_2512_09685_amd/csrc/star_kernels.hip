@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const float mu, const float wd, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
-                                                     double* __restrict__ partials) {
+                                                     double* __restrict__ partials, const InlineTables inl) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
     extern __shared__ float lds[];
     float* s_coef = lds;
@@ -219,10 +219,18 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
     uint32_t* s_mask = reinterpret_cast<uint32_t*>(s_lr + U);
     float* s_wave = reinterpret_cast<float*>(s_mask + U);
     float* s_nacc = s_wave + (NORMS ? (kBlock / 64) * U : 0);
-    for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
-    for (int i = threadIdx.x; i < U; i += kBlock) {
-        s_lr[i] = t_lr[i];
-        s_mask[i] = t_mask[i];
+    if (t_coef) {
+        for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
+        for (int i = threadIdx.x; i < U; i += kBlock) {
+            s_lr[i] = t_lr[i];
+            s_mask[i] = t_mask[i];
+        }
+    } else {  // small tables ride in the kernel arguments
+        for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = inl.coef[i];
+        for (int i = threadIdx.x; i < U; i += kBlock) {
+            s_lr[i] = inl.lr[i];
+            s_mask[i] = inl.mask[i];
+        }
     }
     if constexpr (NORMS)
         for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
@@ -392,7 +400,7 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
                        a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,
-                       a.partials);
+                       a.partials, a.coef ? InlineTables() : *a.inl);
     return hipGetLastError();
 }
 

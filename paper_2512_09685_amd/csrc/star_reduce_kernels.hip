@@ -20,17 +20,25 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
                                                              void* const* __restrict__ t_out, const int U,
                                                              const int out_bf16, const int64_t P, const int vec_ok,
                                                              const int norms, const int span_g, const int span_k,
-                                                             double* __restrict__ partials) {
+                                                             double* __restrict__ partials, const InlineTables inl) {
     extern __shared__ uint64_t lds64[];
     uint64_t* s_out = lds64;
     float* s_coef = reinterpret_cast<float*>(s_out + U);
     uint32_t* s_mask = reinterpret_cast<uint32_t*>(s_coef + U * W);
     float* s_wave = reinterpret_cast<float*>(s_mask + U);
     float* s_nacc = s_wave + (norms ? (kBlock / 64) * U : 0);
-    for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
-    for (int i = threadIdx.x; i < U; i += kBlock) {
-        s_mask[i] = t_mask[i];
-        s_out[i] = reinterpret_cast<uint64_t>(t_out[i]);
+    if (t_coef) {
+        for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
+        for (int i = threadIdx.x; i < U; i += kBlock) {
+            s_mask[i] = t_mask[i];
+            s_out[i] = reinterpret_cast<uint64_t>(t_out[i]);
+        }
+    } else {  // small tables ride in the kernel arguments
+        for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = inl.coef[i];
+        for (int i = threadIdx.x; i < U; i += kBlock) {
+            s_mask[i] = inl.mask[i];
+            s_out[i] = reinterpret_cast<uint64_t>(inl.out[i]);
+        }
     }
     if (norms)
         for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
@@ -129,7 +137,8 @@ hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* g
                                      W * (int)sizeof(typename R::vec), 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.rows, a.coef, a.mask, a.out, a.U,
-                       a.out_dtype == STAR_BF16 ? 1 : 0, a.P, a.vec_ok, a.norms, g.span_g, g.span_k, a.partials);
+                       a.out_dtype == STAR_BF16 ? 1 : 0, a.P, a.vec_ok, a.norms, g.span_g, g.span_k, a.partials,
+                       a.coef ? InlineTables() : *a.inl);
     return hipGetLastError();
 }
 
