@@ -217,8 +217,7 @@ def main():
             if name == a.workload:
                 per_config.append(head)
             else:
-                per_config.append(measure(workloads.WORKLOADS[name], max(3, min(a.steps, 10)), min(a.warmup, 2),
-                                          torch, star, workloads, a.op))
+                per_config.append(measure(workloads.WORKLOADS[name], a.steps, a.warmup, torch, star, workloads, a.op))
     out = {
         "metric": "group_updates_per_s" if a.op != "reduce" else "group_aggregations_per_s",
         "value": head["group_updates_per_s"],

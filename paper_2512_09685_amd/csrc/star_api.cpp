@@ -61,6 +61,7 @@ struct Slot {
     bool used = false;
 };
 
+constexpr double kResidentStateBytes = 128.0 * 1024 * 1024;
 constexpr int kSlots = 8;
 Slot g_slots[kSlots];
 int g_next_slot = 0;
@@ -97,15 +98,8 @@ void free_slot(Slot& s) {
     s = Slot();
 }
 
-// Hands out the next slot with at least the asked capacities (g_mu held).
-star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles, Slot** out) {
-    Slot& s = g_slots[g_next_slot];
-    g_next_slot = (g_next_slot + 1) % kSlots;
-    if (s.used && s.device != device) free_slot(s);
-    if (s.used) STAR_HIP(hipEventSynchronize(s.done));
-    if (!s.done) STAR_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
-    s.device = device;
-    s.used = true;
+// Grows one slot to the asked capacities (its previous work has completed).
+star_status grow_slot(Slot& s, size_t table_bytes, size_t partial_doubles) {
     if (table_bytes > s.table_cap) {
         if (s.host) STAR_HIP(hipHostFree(s.host));
         if (s.dev) STAR_HIP(hipFree(s.dev));
@@ -122,6 +116,38 @@ star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles,
         s.partial_cap = 0;
         STAR_HIP(hipMalloc(reinterpret_cast<void**>(&s.partials), partial_doubles * sizeof(double)));
         s.partial_cap = partial_doubles;
+    }
+    return STAR_OK;
+}
+
+// Hands out the next slot with at least the asked capacities (g_mu held).
+// Whenever a slot has to grow, the idle ones are grown with it, so that the
+// allocations (which synchronise the device) happen in one call and not
+// spread over the next seven.
+star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles, Slot** out) {
+    Slot& s = g_slots[g_next_slot];
+    g_next_slot = (g_next_slot + 1) % kSlots;
+    if (s.used && s.device != device) free_slot(s);
+    if (s.used) STAR_HIP(hipEventSynchronize(s.done));
+    if (!s.done) STAR_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    const bool grows = table_bytes > s.table_cap || partial_doubles > s.partial_cap;
+    s.device = device;
+    s.used = true;
+    star_status st = grow_slot(s, table_bytes, partial_doubles);
+    if (st != STAR_OK) return st;
+    if (grows) {
+        for (Slot& o : g_slots) {
+            if (&o == &s || (o.used && o.device != device)) continue;
+            if (o.used && hipEventQuery(o.done) != hipSuccess) continue;   // busy: it grows when its turn comes
+            if (!o.done) STAR_HIP(hipEventCreateWithFlags(&o.done, hipEventDisableTiming));
+            st = grow_slot(o, table_bytes, partial_doubles);
+            if (st != STAR_OK) return st;
+            if (!o.used) {
+                o.device = device;
+                o.used = true;
+                STAR_HIP(hipEventRecord(o.done, nullptr));   // a completed event, so that waiting on it is valid
+            }
+        }
     }
     *out = &s;
     return STAR_OK;
@@ -194,6 +220,9 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const int grid_cap = star::kGridCap;
 
     const int grad_bytes = grad_dtype == STAR_F32 ? 4 : 2;
+    // params + momentum of a shard up to this size stay resident in the Infinity Cache between calls
+    int stream_state = (double)P * 8.0 > kResidentStateBytes ? 1 : 0;
+    if (const char* e = std::getenv("STAR_TUNE_STREAM")) stream_state = std::atoi(e);   // TUNING ONLY
     const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice);
     const int Wp = star::padded_rows(Wc);
 
@@ -204,12 +233,6 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
         rows.p[k] = grad_rows[plan.row_of[std::min(k, Wc - 1)]];
         if (k < Wc && !aligned16(rows.p[k])) vec_ok = false;
     }
-
-    std::lock_guard<std::mutex> lock(g_mu);
-    const TableLayout lay = table_layout(U, Wp);
-    Slot* slot = nullptr;
-    st = acquire_slot(device, lay.total, want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
-    if (st != STAR_OK) return st;
 
     // tables of the step-by-step kernel: in the kernel arguments when small, else staged through the slot
     const bool seq_inline = route != star::Route::Affine && star::tables_fit_inline(U, Wp);
@@ -223,8 +246,21 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     }
     const bool need_seq_tables = route != star::Route::Affine && !seq_inline;
     const bool need_gram_coef = want_norms && route == star::Route::Affine;
-    char* h = static_cast<char*>(slot->host);
-    char* d = static_cast<char*>(slot->dev);
+
+    // a workspace slot only when something has to live in it (tables, norm partials)
+    const TableLayout lay = table_layout(U, Wp);
+    const bool need_slot = need_seq_tables || need_gram_coef || want_norms;
+    std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
+    Slot* slot = nullptr;
+    if (need_slot) {
+        lock.lock();
+        st = acquire_slot(device, (need_seq_tables || need_gram_coef) ? lay.total : 0,
+                          want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
+        if (st != STAR_OK) return st;
+    }
+    char* h = slot ? static_cast<char*>(slot->host) : nullptr;
+    char* d = slot ? static_cast<char*>(slot->dev) : nullptr;
+    double* partials = slot ? slot->partials : nullptr;
     if (need_seq_tables) {
         float* c32 = reinterpret_cast<float*>(h + lay.coef32);
         float* l32 = reinterpret_cast<float*>(h + lay.lr32);
@@ -271,13 +307,14 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.vec_ok = vec_ok ? 1 : 0;
             a.publish = update ? publish : nullptr;
             a.publish_dtype = publish_dtype;
-            a.partials = slot->partials;
+            a.stream_state = stream_state;
+            a.partials = partials;
             e = star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
             if (gram) {
                 const int ng = Wp * (Wp + 1) / 2;
-                double* gamma = slot->partials + (size_t)ng * grid;
-                e = star::launch_reduce(slot->partials, ng, grid, gamma, nullptr, stream);
+                double* gamma = partials + (size_t)ng * grid;
+                e = star::launch_reduce(partials, ng, grid, gamma, nullptr, stream);
                 if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
                 e = star::launch_gram_norms(gamma, reinterpret_cast<const double*>(d + lay.coef64), U, Wp, norms_out,
                                             stream);
@@ -296,8 +333,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.momentum = momentum;
             a.rows = rows;
             a.coef = seq_inline ? nullptr : reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
-            a.lr = reinterpret_cast<const float*>(d + lay.lr32) + u0;
-            a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
+            a.lr = seq_inline ? nullptr : reinterpret_cast<const float*>(d + lay.lr32) + u0;
+            a.mask = seq_inline ? nullptr : reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
             a.inl = &inl;
             a.U = n;
             a.mu = (float)plan.mu;
@@ -306,16 +343,17 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.vec_ok = vec_ok ? 1 : 0;
             a.publish = (seq_update && u0 + n == U) ? publish : nullptr;   // the last launch holds the final params
             a.publish_dtype = publish_dtype;
-            a.partials = slot->partials;
+            a.stream_state = stream_state;
+            a.partials = partials;
             e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");
             if (want_norms) {
-                e = star::launch_reduce(slot->partials, n, grid, nullptr, norms_out + u0, stream);
+                e = star::launch_reduce(partials, n, grid, nullptr, norms_out + u0, stream);
                 if (e != hipSuccess) return hip_fail(e, "launch of the norm reduction");
             }
         }
     }
-    STAR_HIP(hipEventRecord(slot->done, stream));
+    if (slot) STAR_HIP(hipEventRecord(slot->done, stream));
     return STAR_OK;
 }
 
@@ -393,8 +431,8 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         star::ReduceArgs a;
         a.rows = rows;
         a.coef = use_inline ? nullptr : reinterpret_cast<const float*>(d + lay.coef32) + (size_t)u0 * Wp;
-        a.mask = reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
-        a.out = reinterpret_cast<void* const*>(d + lay.outptr) + u0;
+        a.mask = use_inline ? nullptr : reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
+        a.out = use_inline ? nullptr : reinterpret_cast<void* const*>(d + lay.outptr) + u0;
         a.inl = &inl;
         a.U = n;
         a.out_dtype = out_dtype;

@@ -59,6 +59,24 @@ __device__ __forceinline__ void store_streaming(f32x4 x, f32x4* dst) {
     __builtin_nontemporal_store(x, dst);
 }
 
+// Params / momentum access.  A shard whose state outgrows the 256 MB Infinity
+// Cache is streamed (non-temporal loads and stores: nothing of it would
+// survive until the next call anyway, and the hint is worth ~6 % on the mixed
+// read / read-modify-write traffic); a small shard is accessed normally, so
+// that it stays cache-resident from one call to the next.
+__device__ __forceinline__ f32x4 load_state(const float* base, int64_t idx4, int streaming) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(base) + idx4;
+    return streaming ? __builtin_nontemporal_load(p) : *p;
+}
+__device__ __forceinline__ void store_state(f32x4 x, float* base, int64_t idx4, int streaming) {
+    f32x4* p = reinterpret_cast<f32x4*>(base) + idx4;
+    asm volatile("" : "+v"(x));
+    if (streaming)
+        __builtin_nontemporal_store(x, p);
+    else
+        *p = x;
+}
+
 // fp32 -> bf16, round to nearest even; NaN stays NaN (quiet bit forced).
 __device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
     uint32_t b = __float_as_uint(x);
