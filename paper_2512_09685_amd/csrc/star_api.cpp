@@ -61,7 +61,6 @@ struct Slot {
     bool used = false;
 };
 
-constexpr double kResidentStateBytes = 128.0 * 1024 * 1024;
 constexpr int kSlots = 8;
 Slot g_slots[kSlots];
 int g_next_slot = 0;
@@ -220,9 +219,6 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const int grid_cap = star::kGridCap;
 
     const int grad_bytes = grad_dtype == STAR_F32 ? 4 : 2;
-    // params + momentum of a shard up to this size stay resident in the Infinity Cache between calls
-    int stream_state = (double)P * 8.0 > kResidentStateBytes ? 1 : 0;
-    if (const char* e = std::getenv("STAR_TUNE_STREAM")) stream_state = std::atoi(e);   // TUNING ONLY
     const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice);
     const int Wp = star::padded_rows(Wc);
 
@@ -307,7 +303,6 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.vec_ok = vec_ok ? 1 : 0;
             a.publish = update ? publish : nullptr;
             a.publish_dtype = publish_dtype;
-            a.stream_state = stream_state;
             a.partials = partials;
             e = star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
@@ -343,7 +338,6 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.vec_ok = vec_ok ? 1 : 0;
             a.publish = (seq_update && u0 + n == U) ? publish : nullptr;   // the last launch holds the final params
             a.publish_dtype = publish_dtype;
-            a.stream_state = stream_state;
             a.partials = partials;
             e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");

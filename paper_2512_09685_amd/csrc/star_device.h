@@ -59,22 +59,14 @@ __device__ __forceinline__ void store_streaming(f32x4 x, f32x4* dst) {
     __builtin_nontemporal_store(x, dst);
 }
 
-// Params / momentum access.  A shard whose state outgrows the 256 MB Infinity
-// Cache is streamed (non-temporal loads and stores: nothing of it would
-// survive until the next call anyway, and the hint is worth ~6 % on the mixed
-// read / read-modify-write traffic); a small shard is accessed normally, so
-// that it stays cache-resident from one call to the next.
-__device__ __forceinline__ f32x4 load_state(const float* base, int64_t idx4, int streaming) {
-    const f32x4* p = reinterpret_cast<const f32x4*>(base) + idx4;
-    return streaming ? __builtin_nontemporal_load(p) : *p;
+// Params / momentum access: streamed (non-temporal), worth ~6 % on the mixed read / read-modify-write
+// traffic.  The hint does not keep a small shard from staying in the 256 MB Infinity Cache between
+// calls: shards with params + momentum up to that size ran equally fast with and without it.
+__device__ __forceinline__ f32x4 load_state(const float* base, int64_t idx4) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(base) + idx4);
 }
-__device__ __forceinline__ void store_state(f32x4 x, float* base, int64_t idx4, int streaming) {
-    f32x4* p = reinterpret_cast<f32x4*>(base) + idx4;
-    asm volatile("" : "+v"(x));
-    if (streaming)
-        __builtin_nontemporal_store(x, p);
-    else
-        *p = x;
+__device__ __forceinline__ void store_state(f32x4 x, float* base, int64_t idx4) {
+    store_streaming(x, reinterpret_cast<f32x4*>(base) + idx4);
 }
 
 // fp32 -> bf16, round to nearest even; NaN stays NaN (quiet bit forced).

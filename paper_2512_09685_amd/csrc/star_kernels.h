@@ -56,7 +56,6 @@ struct SeqArgs {
     int32_t vec_ok;        // all buffers 16-byte aligned
     void* publish;         // device copy of the new params (P elements), or null
     int32_t publish_dtype; // star_dtype of that copy
-    int32_t stream_state;  // params / momentum bypass the caches (large shards)
     double* partials;      // device [U][grid] sums of gbar^2 per block (norms only)
 };
 
@@ -78,7 +77,6 @@ struct AffArgs {
     int32_t vec_ok;
     void* publish;          // device copy of the new params (P elements), or null
     int32_t publish_dtype;  // star_dtype of that copy
-    int32_t stream_state;   // params / momentum bypass the caches (large shards)
     double* partials;  // device [Wp(Wp+1)/2][grid] pairwise-product sums per block (gram only)
 };
 

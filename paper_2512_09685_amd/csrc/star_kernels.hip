@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
-                                                     const int stream_state, double* __restrict__ partials) {
+                                                     double* __restrict__ partials) {
     constexpr int VEC = R::VEC;
     constexpr int NG = W * (W + 1) / 2;
     float acc[GRAM ? NG : 1];
@@ -101,8 +101,8 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
         if constexpr (UPDATE) {
 #pragma unroll
             for (int q = 0; q < VEC / 4; ++q) {
-                const f32x4 pq = load_state(params, c * (VEC / 4) + q, stream_state);
-                const f32x4 vq = load_state(momentum, c * (VEC / 4) + q, stream_state);
+                const f32x4 pq = load_state(params, c * (VEC / 4) + q);
+                const f32x4 vq = load_state(momentum, c * (VEC / 4) + q);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     pe[4 * q + k] = pq[k];
@@ -125,8 +125,8 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
             for (int q = 0; q < VEC / 4; ++q) {
                 f32x4 pq = {pe[4 * q], pe[4 * q + 1], pe[4 * q + 2], pe[4 * q + 3]};
                 f32x4 vq = {ve[4 * q], ve[4 * q + 1], ve[4 * q + 2], ve[4 * q + 3]};
-                store_state(pq, params, c * (VEC / 4) + q, stream_state);
-                store_state(vq, momentum, c * (VEC / 4) + q, stream_state);
+                store_state(pq, params, c * (VEC / 4) + q);
+                store_state(vq, momentum, c * (VEC / 4) + q);
                 if (publish) publish_chunk(pq, publish, publish_bf16, c * (VEC / 4) + q);
             }
         }
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const float mu, const float wd, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
-                                                     const int stream_state, double* __restrict__ partials,
+                                                     double* __restrict__ partials,
                                                      const InlineTables inl) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
     extern __shared__ float lds[];
@@ -247,8 +247,8 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
         for (int w = 0; w < W; ++w) raw[w] = R::load(rows.p[w], c);
         float p[4] = {0, 0, 0, 0}, v[4] = {0, 0, 0, 0};
         if constexpr (UPDATE) {
-            const f32x4 pv = load_state(params, c, stream_state);
-            const f32x4 vv = load_state(momentum, c, stream_state);
+            const f32x4 pv = load_state(params, c);
+            const f32x4 vv = load_state(momentum, c);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 p[k] = pv[k];
@@ -271,8 +271,8 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                 pv[k] = p[k];
                 vv[k] = v[k];
             }
-            store_state(pv, params, c, stream_state);
-            store_state(vv, momentum, c, stream_state);
+            store_state(pv, params, c);
+            store_state(vv, momentum, c);
             if (publish) publish_chunk(pv, publish, publish_bf16, c);
         }
     }
@@ -401,7 +401,7 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
                        a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,
-                       a.stream_state, a.partials, a.coef ? InlineTables() : *a.inl);
+                       a.partials, a.coef ? InlineTables() : *a.inl);
     return hipGetLastError();
 }
 
@@ -411,7 +411,7 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     const Geometry g = pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
-                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.stream_state, a.partials);
+                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials);
     return hipGetLastError();
 }
 
