@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -42,7 +43,7 @@ int initial_kernel_choice() {
     return STAR_KERNEL_AUTO;
 }
 
-int g_kernel_choice = initial_kernel_choice();
+std::atomic<int> g_kernel_choice{initial_kernel_choice()};
 
 // ---------------------------------------------------------------- workspace
 // A ring of slots.  One call uses one slot: a pinned host staging buffer and a
@@ -219,7 +220,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const int grid_cap = star::kGridCap;
 
     const int grad_bytes = grad_dtype == STAR_F32 ? 4 : 2;
-    const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice);
+    const star::Route route = star::choose_route(plan, grad_bytes, update, want_norms, g_kernel_choice.load());
     const int Wp = star::padded_rows(Wc);
 
     // rows in compact order; padding rows repeat the last row with zero coefficients
@@ -568,7 +569,7 @@ star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hpar
     std::string msg;
     star_status st = star::build_plan(W, upd, hp, 0, want_norms != 0, &plan, &msg);
     if (st != STAR_OK) return set_err(st, msg);
-    const star::Route r = star::choose_route(plan, 4, true, want_norms != 0, g_kernel_choice);
+    const star::Route r = star::choose_route(plan, 4, true, want_norms != 0, g_kernel_choice.load());
     if (kernel_out) *kernel_out = r == star::Route::Seq ? STAR_KERNEL_SEQ : STAR_KERNEL_AFFINE;
     if (fma_seq) *fma_seq = plan.fma_seq;
     if (fma_affine) *fma_affine = plan.fma_affine;
@@ -579,7 +580,7 @@ star_status star_set_kernel(int32_t kernel) {
     g_err.clear();
     if (kernel != STAR_KERNEL_AUTO && kernel != STAR_KERNEL_SEQ && kernel != STAR_KERNEL_AFFINE)
         return set_err(STAR_ERR_KERNEL, "unknown kernel choice");
-    g_kernel_choice = kernel;
+    g_kernel_choice.store(kernel);
     return STAR_OK;
 }
 

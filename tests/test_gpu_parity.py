@@ -284,3 +284,58 @@ def test_selector_groups_drive_the_update():
     for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
         p, v, n = gpu_update(p0, v0, rows, r["offsets"], r["members"], kernel=kern, **hp)
         check(p, v, n, ep, ev, en, "f32", f"selector kern={kern}")
+
+
+def test_concurrent_host_threads_on_their_own_streams():
+    """Four host threads, each with its own stream and shard, call the library at
+    the same time; every result must equal the single-threaded one bit for bit."""
+    import threading
+    rng = np.random.default_rng(15)
+    W, P, U = 8, 200003, 12
+    jobs = []
+    for t in range(4):
+        rows = rand_rows(rng, W, P, "f32")
+        offs, mem, st = rand_stream(rng, W, U, stale=3)
+        p0 = rng.standard_normal(P).astype(np.float32)
+        jobs.append((rows, to_dev_rows(rows), offs, mem, st, p0))
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+
+    def run_one(job, stream, out):
+        rows, drows, offs, mem, st, p0 = job
+        p = torch.from_numpy(p0).cuda()
+        v = torch.zeros(P, device="cuda")
+        n = torch.zeros(U, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(5):                       # several calls, so that the threads really overlap
+            star.star_group_update(p, v, drows, star.UpdateStream(offs, mem, st), norms_out=n, stream=stream, **hp)
+        stream.synchronize()
+        out.append((p.cpu().numpy(), v.cpu().numpy(), n.cpu().numpy()))
+
+    serial = []
+    for job in jobs:
+        o = []
+        run_one(job, torch.cuda.Stream(), o)
+        serial.append(o[0])
+    results = [[] for _ in jobs]
+    threads = [threading.Thread(target=run_one, args=(job, torch.cuda.Stream(), results[i])) for i, job in enumerate(jobs)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for s, r in zip(serial, results):
+        for a, b in zip(s, r[0]):
+            assert np.array_equal(a, b)
+
+
+def test_very_long_stream():
+    """Thousands of updates in one call: the collapsed route composes them on the host."""
+    rng = np.random.default_rng(16)
+    W, P, U = 6, 4099, 5000
+    rows = rand_rows(rng, W, P, "f32", std=1e-3)
+    offs, mem, _ = rand_stream(rng, W, U)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=1e-3, momentum_coef=0.9, weight_decay=1e-4, want_norms=True)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, **hp)
+    p, v, n = gpu_update(p0, v0, rows, offs, mem, **hp)
+    check(p, v, n, ep, ev, en, "f32", "U=5000")

@@ -162,3 +162,30 @@ def test_noise_scale_host_function():
     ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
     assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(17), ctypes.c_void_p(0x9000), None) == 2
     assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(4), None, None) == 1
+
+
+def test_affine_map_property_random_streams():
+    """Property test: for arbitrary small streams and hyper-parameters the collapsed
+    map reproduces the sequential oracle."""
+    from hypothesis import given, settings, strategies as hst
+
+    @settings(max_examples=60, deadline=None)
+    @given(hst.integers(1, 8), hst.integers(1, 12), hst.integers(0, 2 ** 31 - 1), hst.floats(0.0, 0.99),
+           hst.floats(0.0, 0.5), hst.booleans())
+    def prop(W, U, seed, mu, wd, scale):
+        rng = np.random.default_rng(seed)
+        P = 7
+        rows = [rng.standard_normal(P).astype(np.float32) for _ in range(W)]
+        offs, mem, st = _rand_stream(rng, W, U, stale=3)
+        lrs = rng.uniform(0.0, 0.3, U).astype(np.float32)
+        p0, v0 = rng.standard_normal(P).astype(np.float32), rng.standard_normal(P).astype(np.float32)
+        us = star.UpdateStream(offs, mem, st, None, lrs)
+        M, B = star.star_plan_affine(W, us, lr=0.0, momentum_coef=mu, weight_decay=wd, wmode="stale",
+                                     scale_lr_by_group=scale)
+        p, v, _ = so.group_update(p0, v0, rows, offs, mem, lr=0.0, momentum_coef=mu, weight_decay=wd, wmode="stale",
+                                  staleness=st, lr_per_update=lrs, scale_lr_by_group=scale, mode="f64")
+        x = M @ np.stack([p0, v0]).astype(np.float64) + B @ np.stack(rows).astype(np.float64)
+        np.testing.assert_allclose(x[0], p, rtol=0, atol=1e-11)
+        np.testing.assert_allclose(x[1], v, rtol=0, atol=1e-11)
+
+    prop()
