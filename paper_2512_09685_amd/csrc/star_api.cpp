@@ -59,7 +59,7 @@ struct Slot {
     double* partials = nullptr;
     size_t partial_cap = 0;   // doubles
     hipEvent_t done = nullptr;
-    bool used = false;
+    bool pending = false;     // `done` has been recorded after work that uses this slot
 };
 
 constexpr int kSlots = 8;
@@ -89,7 +89,7 @@ star_status device_info(int* device, int* num_cu) {
 
 void free_slot(Slot& s) {
     if (s.done) {
-        (void)hipEventSynchronize(s.done);
+        if (s.pending) (void)hipEventSynchronize(s.done);
         (void)hipEventDestroy(s.done);
     }
     if (s.host) (void)hipHostFree(s.host);
@@ -127,31 +127,38 @@ star_status grow_slot(Slot& s, size_t table_bytes, size_t partial_doubles) {
 star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles, Slot** out) {
     Slot& s = g_slots[g_next_slot];
     g_next_slot = (g_next_slot + 1) % kSlots;
-    if (s.used && s.device != device) free_slot(s);
-    if (s.used) STAR_HIP(hipEventSynchronize(s.done));
+    if (s.device != -1 && s.device != device) free_slot(s);   // its memory lives on another device
+    if (s.pending) STAR_HIP(hipEventSynchronize(s.done));
+    s.pending = false;
     if (!s.done) STAR_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
     const bool grows = table_bytes > s.table_cap || partial_doubles > s.partial_cap;
     s.device = device;
-    s.used = true;
     star_status st = grow_slot(s, table_bytes, partial_doubles);
     if (st != STAR_OK) return st;
     if (grows) {
         for (Slot& o : g_slots) {
-            if (&o == &s || (o.used && o.device != device)) continue;
-            if (o.used && hipEventQuery(o.done) != hipSuccess) continue;   // busy: it grows when its turn comes
-            if (!o.done) STAR_HIP(hipEventCreateWithFlags(&o.done, hipEventDisableTiming));
+            if (&o == &s || (o.device != -1 && o.device != device)) continue;
+            if (o.pending && hipEventQuery(o.done) != hipSuccess) continue;   // busy: it grows when its turn comes
+            o.pending = false;
+            o.device = device;
             st = grow_slot(o, table_bytes, partial_doubles);
             if (st != STAR_OK) return st;
-            if (!o.used) {
-                o.device = device;
-                o.used = true;
-                STAR_HIP(hipEventRecord(o.done, nullptr));   // a completed event, so that waiting on it is valid
-            }
         }
     }
     *out = &s;
     return STAR_OK;
 }
+
+// On every way out of a call, marks its slot busy until everything enqueued on
+// the stream so far has run (also after a failed launch: earlier launches of
+// the same call may still be using the slot).
+struct SlotRelease {
+    Slot* slot = nullptr;
+    hipStream_t stream = nullptr;
+    ~SlotRelease() {
+        if (slot && hipEventRecord(slot->done, stream) == hipSuccess) slot->pending = true;
+    }
+};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -255,6 +262,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
                           want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
         if (st != STAR_OK) return st;
     }
+    SlotRelease release{slot, stream};
     char* h = slot ? static_cast<char*>(slot->host) : nullptr;
     char* d = slot ? static_cast<char*>(slot->dev) : nullptr;
     double* partials = slot ? slot->partials : nullptr;
@@ -348,7 +356,6 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             }
         }
     }
-    if (slot) STAR_HIP(hipEventRecord(slot->done, stream));
     return STAR_OK;
 }
 
@@ -399,6 +406,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
     Slot* slot = nullptr;
     st = acquire_slot(device, lay.total, want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
     if (st != STAR_OK) return st;
+    SlotRelease release{slot, stream};
     char* h = static_cast<char*>(slot->host);
     char* d = static_cast<char*>(slot->dev);
     const bool use_inline = star::tables_fit_inline(U, Wp);
@@ -443,7 +451,6 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
             if (e != hipSuccess) return hip_fail(e, "launch of the norm reduction");
         }
     }
-    STAR_HIP(hipEventRecord(slot->done, stream));
     return STAR_OK;
 }
 
@@ -505,6 +512,7 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     Slot* slot = nullptr;
     st = acquire_slot(device, 0, partial_doubles_needed(W, 1, star::kGridCap), &slot);
     if (st != STAR_OK) return st;
+    SlotRelease release{slot, stream};
     a.P = P;
     a.vec_ok = vec_ok ? 1 : 0;
     a.partials = slot->partials;
@@ -517,7 +525,6 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
     e = star::launch_gram_unpack(gamma, W, gram_out, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram unpack kernel");
-    STAR_HIP(hipEventRecord(slot->done, stream));
     return STAR_OK;
 }
 
@@ -598,8 +605,7 @@ const char* star_version(void) { return "libstar 0.1 (gfx950)"; }
 
 void star_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mu);
-    for (Slot& s : g_slots)
-        if (s.used || s.done) free_slot(s);
+    for (Slot& s : g_slots) free_slot(s);
     g_next_slot = 0;
 }
 
