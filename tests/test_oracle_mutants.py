@@ -28,6 +28,10 @@ MUTANTS = [
      "double d = gbar + wd * params[j];\n            sumsq += d * d;"),
     ("bf16_shift", "<< 16; /* bf16", "<< 15; /* bf16"),
     ("lr_of_first_update", "(double)up->lr[u]", "(double)up->lr[0]"),
+    ("reduce_output_row_index", "out[(int64_t)u * P + j] = gbar;", "out[j] = gbar;"),
+    ("gram_uses_one_row_twice", "s += grad_at(rows[a], grad_dtype, j) * grad_at(rows[b], grad_dtype, j);",
+     "s += grad_at(rows[a], grad_dtype, j) * grad_at(rows[a], grad_dtype, j);"),
+    ("gram_transposed_store", "out[(int64_t)a * W + b] = s;", "out[(int64_t)a * W + b] = (a <= b) ? s : 0.0;"),
     ("decay_after_step", "double d = gbar + wd * params[j];\n            momentum[j] = mu * momentum[j] + d;\n            params[j] = params[j] - lr * momentum[j];",
      "momentum[j] = mu * momentum[j] + gbar;\n            params[j] = params[j] - lr * momentum[j];\n            params[j] = params[j] - lr * wd * params[j];"),
 ]
