@@ -103,3 +103,50 @@ def test_full_size_workload(name):
         del host_rows, norms, norms2
     del p, v, rows
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["bert_base", "vgg16"])
+def test_full_size_publish_and_reduce(name):
+    """The widened entry points at full workload size, on sampled elements:
+    update with a bf16 copy of the new parameters, and one full-group
+    aggregation with bf16 output."""
+    wl = workloads.WORKLOADS[name]
+    print(f"full-size publish/reduce {name}: P={wl.P} W={wl.W}", flush=True)
+    rng = np.random.default_rng(321)
+    idx = sample_indices(wl.P, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    p = workloads.make_params(wl, 0, "cuda")
+    v = workloads.make_momentum(wl, "cuda")
+    p0, v0 = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
+    rows = workloads.make_grad_rows(wl, 0, 0, "cuda")
+    s = workloads.make_update_stream(wl, 0, 0)
+    us = star.UpdateStream(s["offsets"], s["members"], s["staleness"])
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    pub = torch.zeros(wl.P, dtype=torch.bfloat16, device="cuda")
+    star.star_group_update_publish(p, v, rows, us, pub, **hp)
+    torch.cuda.synchronize()
+    sub = rows_at(rows, idx_dev)
+    ep, ev, _ = so.group_update(p0, v0, sub, s["offsets"], s["members"], staleness=s["staleness"], **hp)
+    tol = TOL[wl.grad_dtype]
+    assert so.max_rel_err(p[idx_dev].cpu().numpy(), ep) <= tol
+    assert torch.equal(pub[idx_dev].cpu(), p[idx_dev].cpu().to(torch.bfloat16))
+    assert so.max_rel_err(pub[idx_dev].float().cpu().numpy(), ep) <= 4e-3
+    del pub
+    # aggregation of all W rows, bf16 out, norm on
+    full_offs = np.array([0, wl.W], np.int32)
+    full_mem = np.arange(wl.W, dtype=np.int32)
+    out = [torch.zeros(wl.P, dtype=torch.bfloat16, device="cuda")]
+    n = torch.zeros(1, device="cuda")
+    star.star_group_reduce(out, rows, star.UpdateStream(full_offs, full_mem), norms_out=n)
+    torch.cuda.synchronize()
+    eo = so.group_reduce(sub, full_offs, full_mem)
+    assert so.max_rel_err(out[0][idx_dev].float().cpu().numpy(), eo[0]) <= 4e-3
+    # the norm against the Gram matrix of the rows where that is built (W <= 16), else against the output itself
+    if wl.W <= 16:
+        g = torch.zeros((wl.W, wl.W), dtype=torch.float64, device="cuda")
+        star.star_group_gram(rows, g)
+        torch.cuda.synchronize()
+        ref = float(torch.sqrt(g.sum()).item()) / wl.W
+    else:
+        ref = float(torch.linalg.vector_norm(out[0].float().double()).item())
+    assert abs(n.item() / ref - 1) <= (1e-5 if wl.W <= 16 else 2e-3)
