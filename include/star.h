@@ -89,7 +89,9 @@ typedef enum {
 typedef enum {
     STAR_KERNEL_AUTO = 0,  /* pick by arithmetic cost                                          */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
-    STAR_KERNEL_AFFINE = 2 /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1) */
+    STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1) */
+    STAR_KERNEL_AFFINE_MFMA = 3 /* the same, with the Gram matrix behind the norms formed on the matrix
+                                   cores also for 16 rows or fewer (beyond 16 rows it always is)      */
 } star_kernel;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is
@@ -186,7 +188,7 @@ star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hpar
  * Gram matrix of the gradient rows, Gamma[a][b] = sum_j g_a[j] g_b[j], the
  * quantity the per-group norms are derived from (|| sum_w c_w g_w ||^2 =
  * c^T Gamma c) and the input of the noise-scale estimate below.
- *   grad_rows : host array of W device pointers, all used; 1 <= W <= 16
+ *   grad_rows : host array of W device pointers, all used; 1 <= W <= 32
  *   gram_out  : device double[W*W], row-major, symmetric
  * One pass over the rows; products and per-thread sums in fp32, across
  * workgroups in fp64.
@@ -276,7 +278,7 @@ star_status star_select_mode_ar(int32_t N, const double *iter_time, const double
                                 double *time_out, double *time_table);
 
 /* Force an evaluation for later calls of this process (default AUTO; the
- * environment variable STAR_KERNEL=auto|seq|affine sets the initial value). */
+ * environment variable STAR_KERNEL=auto|seq|affine|affine_mfma sets the initial value). */
 star_status star_set_kernel(int32_t kernel);
 
 /* Bytes of internal device workspace one call of this shape uses. */

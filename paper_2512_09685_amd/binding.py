@@ -16,7 +16,7 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libstar.so")
 
-KERNEL_AUTO, KERNEL_SEQ, KERNEL_AFFINE = 0, 1, 2
+KERNEL_AUTO, KERNEL_SEQ, KERNEL_AFFINE, KERNEL_AFFINE_MFMA = 0, 1, 2, 3
 F32, BF16 = 0, 1
 _WMODES = {"mean": 0, "stale": 1, "explicit": 2}
 STATUS_NAMES = {0: "STAR_OK", 1: "STAR_ERR_NULL", 2: "STAR_ERR_SHAPE", 3: "STAR_ERR_GROUP", 4: "STAR_ERR_HPARAM",

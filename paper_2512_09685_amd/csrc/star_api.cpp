@@ -40,6 +40,7 @@ int initial_kernel_choice() {
     if (!e) return STAR_KERNEL_AUTO;
     if (!std::strcmp(e, "seq")) return STAR_KERNEL_SEQ;
     if (!std::strcmp(e, "affine")) return STAR_KERNEL_AFFINE;
+    if (!std::strcmp(e, "affine_mfma")) return STAR_KERNEL_AFFINE_MFMA;
     return STAR_KERNEL_AUTO;
 }
 
@@ -313,7 +314,10 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish = update ? publish : nullptr;
             a.publish_dtype = publish_dtype;
             a.partials = partials;
-            e = star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
+            // Gram matrix on the vector ALUs up to 16 rows, on the matrix cores beyond (or when asked for)
+            const bool mfma = gram && (Wp > star::kMaxValuGramW || g_kernel_choice.load() == STAR_KERNEL_AFFINE_MFMA);
+            e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
+                     : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
             if (gram) {
                 const int ng = Wp * (Wp + 1) / 2;
@@ -490,11 +494,11 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     g_err.clear();
     if (!grad_rows || !gram_out) return set_err(STAR_ERR_NULL, "grad_rows or gram_out is NULL");
     if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
-    if (W < 1 || W > star::kMaxGramW) return set_err(STAR_ERR_SHAPE, "the Gram matrix is built for 1 to 16 rows");
+    if (W < 1 || W > star::kMaxGramW) return set_err(STAR_ERR_SHAPE, "the Gram matrix is built for 1 to 32 rows");
     if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (P == 0) {
-        hipError_t e0 = star::launch_gram_unpack(nullptr, W, gram_out, stream);
+        hipError_t e0 = star::launch_gram_unpack(nullptr, W, W, gram_out, stream);
         return e0 == hipSuccess ? STAR_OK : hip_fail(e0, "launch of the Gram unpack kernel");
     }
     star::AffArgs a;
@@ -510,20 +514,23 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     if (st != STAR_OK) return st;
     std::lock_guard<std::mutex> lock(g_mu);
     Slot* slot = nullptr;
-    st = acquire_slot(device, 0, partial_doubles_needed(W, 1, star::kGridCap), &slot);
+    st = acquire_slot(device, 0, partial_doubles_needed(star::padded_rows(W), 1, star::kGridCap), &slot);
     if (st != STAR_OK) return st;
     SlotRelease release{slot, stream};
     a.P = P;
     a.vec_ok = vec_ok ? 1 : 0;
     a.partials = slot->partials;
     int grid = 0;
-    hipError_t e = star::launch_affine(W, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
+    const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
+    const bool mfma = Wp > star::kMaxValuGramW || g_kernel_choice.load() == STAR_KERNEL_AFFINE_MFMA;
+    hipError_t e = mfma ? star::launch_affine_mfma(Wp, (int)grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
+                        : star::launch_affine(Wp, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");
-    const int ng = W * (W + 1) / 2;
+    const int ng = Wp * (Wp + 1) / 2;
     double* gamma = slot->partials + (size_t)ng * grid;
     e = star::launch_reduce(slot->partials, ng, grid, gamma, nullptr, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
-    e = star::launch_gram_unpack(gamma, W, gram_out, stream);
+    e = star::launch_gram_unpack(gamma, Wp, W, gram_out, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram unpack kernel");
     return STAR_OK;
 }
@@ -585,7 +592,8 @@ star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hpar
 
 star_status star_set_kernel(int32_t kernel) {
     g_err.clear();
-    if (kernel != STAR_KERNEL_AUTO && kernel != STAR_KERNEL_SEQ && kernel != STAR_KERNEL_AFFINE)
+    if (kernel != STAR_KERNEL_AUTO && kernel != STAR_KERNEL_SEQ && kernel != STAR_KERNEL_AFFINE &&
+        kernel != STAR_KERNEL_AFFINE_MFMA)
         return set_err(STAR_ERR_KERNEL, "unknown kernel choice");
     g_kernel_choice.store(kernel);
     return STAR_OK;

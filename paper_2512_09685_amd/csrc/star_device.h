@@ -143,6 +143,25 @@ __device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
     return s;
 }
 
+// ---------------------------------------------------------------- the collapsed update of one element
+constexpr int kGramFold = 64;  // tiles between folds of the pairwise-product accumulators (power of two)
+
+template <int W>
+__device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W], const AffCoef& cf) {
+    // increment of p first, one final add: p is perturbed by one rounding of p itself
+    float inc = cf.dp * p;
+    inc = __builtin_fmaf(cf.m01, v, inc);
+    float nv = cf.m10 * p;
+    nv = __builtin_fmaf(cf.m11, v, nv);
+#pragma unroll
+    for (int w = 0; w < W; ++w) {  // ascending worker id
+        inc = __builtin_fmaf(cf.b0[w], g[w], inc);
+        nv = __builtin_fmaf(cf.b1[w], g[w], nv);
+    }
+    p = p + inc;
+    v = nv;
+}
+
 // ================================================================= host side of a launch
 // Launch geometry: G workgroups per span, K tiles per workgroup, and the grid.
 struct Geometry {

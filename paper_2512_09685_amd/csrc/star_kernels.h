@@ -10,7 +10,7 @@
 namespace star {
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
-constexpr int kGridCap = 4096;       // most workgroups a norm-reducing launch uses (sizes the partial buffer)
+constexpr int kGridCap = 1024;       // most workgroups a norm-reducing launch uses (sizes the partial buffer)
 
 struct RowPtrs {
     const void* p[STAR_MAX_WORKERS];
@@ -84,6 +84,10 @@ struct AffArgs {
 hipError_t launch_affine(int Wp, int dtype, bool update, bool gram, const AffArgs& a, int num_cu, int grid_cap,
                          int* grid_out, hipStream_t s);
 
+// The same with the Gram matrix formed on the matrix cores (any Wp up to 32; `gram` is implied).
+hipError_t launch_affine_mfma(int Wp, int dtype, bool update, const AffArgs& a, int num_cu, int grid_cap,
+                              int* grid_out, hipStream_t s);
+
 // out[e] = sum_b partials[e*grid + b] in a fixed order; sums_out (double) and
 // sqrt_out (float, square root of the sum) are each optional.
 hipError_t launch_reduce(const double* partials, int n_out, int grid, double* sums_out, float* sqrt_out,
@@ -93,8 +97,8 @@ hipError_t launch_reduce(const double* partials, int n_out, int grid, double* su
 hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int Wp, float* norms_out,
                              hipStream_t s);
 
-// Packed upper triangle [W(W+1)/2] -> full symmetric [W][W] (all zero when gamma is null).
-hipError_t launch_gram_unpack(const double* gamma, int W, double* out, hipStream_t s);
+// Packed upper triangle over Wp rows [Wp(Wp+1)/2] -> full symmetric [W][W], W <= Wp (all zero when gamma is null).
+hipError_t launch_gram_unpack(const double* gamma, int Wp, int W, double* out, hipStream_t s);
 
 hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
 

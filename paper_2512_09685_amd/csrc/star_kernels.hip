@@ -28,24 +28,6 @@
 namespace star {
 
 // ================================================================= affine kernel
-constexpr int kGramFold = 64;  // tiles between folds of the pairwise-product accumulators (power of two)
-
-template <int W>
-__device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W], const AffCoef& cf) {
-    // increment of p first, one final add: p is perturbed by one rounding of p itself
-    float inc = cf.dp * p;
-    inc = __builtin_fmaf(cf.m01, v, inc);
-    float nv = cf.m10 * p;
-    nv = __builtin_fmaf(cf.m11, v, nv);
-#pragma unroll
-    for (int w = 0; w < W; ++w) {  // ascending worker id
-        inc = __builtin_fmaf(cf.b0[w], g[w], inc);
-        nv = __builtin_fmaf(cf.b1[w], g[w], nv);
-    }
-    p = p + inc;
-    v = nv;
-}
-
 template <int W>
 __device__ __forceinline__ void gram_step(float (&acc)[W * (W + 1) / 2], const float (&g)[W]) {
     int e = 0;
@@ -366,13 +348,14 @@ __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __rest
 
 // Packed upper triangle (row-major, a <= b) -> full symmetric W x W matrix; a zero
 // matrix when gamma is null (empty shard).
-__global__ __launch_bounds__(kBlock) void gram_unpack_kernel(const double* __restrict__ gamma, const int W,
-                                                             double* __restrict__ out) {
+// The packed triangle is over Wp >= W rows (the kernels' padded row count); W x W entries are copied out.
+__global__ __launch_bounds__(kBlock) void gram_unpack_kernel(const double* __restrict__ gamma, const int Wp,
+                                                             const int W, double* __restrict__ out) {
     const int i = blockIdx.x * kBlock + threadIdx.x;
     if (i >= W * W) return;
     const int r = i / W, c = i % W;
     const int a = r < c ? r : c, b = r < c ? c : r;
-    out[i] = gamma ? gamma[a * W - a * (a - 1) / 2 + (b - a)] : 0.0;
+    out[i] = gamma ? gamma[a * Wp - a * (a - 1) / 2 + (b - a)] : 0.0;
 }
 
 __global__ __launch_bounds__(kBlock) void fill_kernel(float* __restrict__ dst, const int64_t n, const float value) {
@@ -494,8 +477,8 @@ hipError_t launch_gram_norms(const double* gamma, const double* coef, int U, int
     return hipGetLastError();
 }
 
-hipError_t launch_gram_unpack(const double* gamma, int W, double* out, hipStream_t s) {
-    hipLaunchKernelGGL(gram_unpack_kernel, dim3((W * W + kBlock - 1) / kBlock), dim3(kBlock), 0, s, gamma, W, out);
+hipError_t launch_gram_unpack(const double* gamma, int Wp, int W, double* out, hipStream_t s) {
+    hipLaunchKernelGGL(gram_unpack_kernel, dim3((W * W + kBlock - 1) / kBlock), dim3(kBlock), 0, s, gamma, Wp, W, out);
     return hipGetLastError();
 }
 

@@ -110,7 +110,10 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
         fma_seq += y + (hp ? 3 : 0) + (want_norms ? 1 : 0);
     }
     plan->fma_seq = fma_seq;
-    plan->fma_affine = (hp ? 2.0 * Wc + 4.0 : 0.0) + (want_norms ? 0.5 * Wc * (Wc + 1) : 0.0);
+    // beyond 16 rows the Gram matrix is formed on the matrix cores: 128 instructions of 64 cycles per
+    // 256 elements and wave, about what 260 vector multiply-adds per element would take
+    const double gram_cost = Wc <= kMaxValuGramW ? 0.5 * Wc * (Wc + 1) : 260.0;
+    plan->fma_affine = (hp ? 2.0 * Wc + 4.0 : 0.0) + (want_norms ? gram_cost : 0.0);
 
     // the collapsed map: x = (p, v);  x' = A_u x + b_u gbar_u,
     //   A_u = [[1 - lr wd, -lr mu], [wd, mu]],  b_u = (-lr, 1),  gbar_u = c_u . g
@@ -142,7 +145,7 @@ Route choose_route(const Plan& plan, int grad_bytes, bool update, bool want_norm
     const int Wc = plan.Wc;
     const bool gram_ok = Wc <= kMaxGramW;
     if (forced == STAR_KERNEL_SEQ) return Route::Seq;
-    if (forced == STAR_KERNEL_AFFINE) return (want_norms && !gram_ok) ? Route::AffinePlusDirectNorms : Route::Affine;
+    if (forced == STAR_KERNEL_AFFINE || forced == STAR_KERNEL_AFFINE_MFMA) return (want_norms && !gram_ok) ? Route::AffinePlusDirectNorms : Route::Affine;
     // Two-term time model per element: HBM bytes at ~5 TB/s against fp32
     // multiply-adds at ~20 T/s sustained (about half of the unpacked vector
     // peak); the larger term bounds a pass.
@@ -153,7 +156,7 @@ Route choose_route(const Plan& plan, int grad_bytes, bool update, bool want_norm
     const double t_seq = pass(row_bytes + state_bytes, plan.fma_seq);
     if (!update) {  // norms only: direct (seq kernel without the step) or Gram
         if (!gram_ok) return Route::Seq;
-        return pass(row_bytes, 0.5 * Wc * (Wc + 1)) < t_seq ? Route::Affine : Route::Seq;
+        return pass(row_bytes, plan.fma_affine) < t_seq ? Route::Affine : Route::Seq;
     }
     double t_aff;
     Route aff;

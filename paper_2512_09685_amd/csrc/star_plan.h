@@ -44,8 +44,10 @@ struct Plan {
 star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode_only,
                        bool want_norms, Plan* plan, std::string* err);
 
-// Largest Wc for which the pairwise-product (Gram) route to the norms is built.
-constexpr int kMaxGramW = 16;
+// Largest Wc for which the pairwise-product (Gram) route to the norms is built: on the vector
+// ALUs (accumulators in registers) and on the matrix cores.
+constexpr int kMaxValuGramW = 16;
+constexpr int kMaxGramW = 32;
 
 enum class Route { Seq, Affine, AffinePlusDirectNorms };
 

@@ -12,14 +12,20 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("W,P", [(1, 5), (2, 1027), (5, 70001), (8, 300007), (16, 123457), (16, 3)])
-def test_gram_matrix(dtype, W, P):
+@pytest.mark.parametrize("mfma", [False, True])
+@pytest.mark.parametrize("W,P", [(1, 5), (2, 1027), (5, 70001), (8, 300007), (16, 123457), (16, 3), (17, 40003),
+                                 (23, 100001), (32, 70007), (32, 2)])
+def test_gram_matrix(dtype, W, P, mfma):
     rng = np.random.default_rng(W * 7 + P)
     rows = rand_rows(rng, W, P, dtype)
     ref = so.gram(rows)
     out = torch.full((W, W), -1.0, dtype=torch.float64, device="cuda")
-    star.star_group_gram(to_dev_rows(rows), out)
-    torch.cuda.synchronize()
+    star.star_set_kernel(star.KERNEL_AFFINE_MFMA if mfma else star.KERNEL_AUTO)
+    try:
+        star.star_group_gram(to_dev_rows(rows), out)
+        torch.cuda.synchronize()
+    finally:
+        star.star_set_kernel(star.KERNEL_AUTO)
     got = out.cpu().numpy()
     assert np.array_equal(got, got.T)
     scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))          # |G_ab| <= sqrt(G_aa G_bb)

@@ -12,7 +12,8 @@ from gpu_util import TOL, gpu_update, rand_rows, rand_stream, to_dev_rows
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = {"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE}
+KERNELS = {"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE,
+           "mfma": star.KERNEL_AFFINE_MFMA}
 
 
 def check(p, v, n, ep, ev, en, dtype, what=""):
@@ -28,7 +29,7 @@ def check(p, v, n, ep, ev, en, dtype, what=""):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("kname", ["seq", "affine", "auto"])
+@pytest.mark.parametrize("kname", ["seq", "affine", "auto", "mfma"])
 @pytest.mark.parametrize("W,P,U,norms", [
     (1, 1, 1, True), (2, 3, 2, False), (4, 5, 10, True), (3, 1023, 7, True), (5, 1025, 12, False),
     (8, 4099, 24, True), (16, 70001, 16, True), (17, 33333, 9, True), (32, 50000, 12, False),
@@ -97,7 +98,7 @@ def test_run_to_run_bitwise_reproducible():
     p0 = rng.standard_normal(P).astype(np.float32)
     v0 = np.zeros(P, np.float32)
     hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale", want_norms=True)
-    for k in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
+    for k in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AFFINE_MFMA):
         a = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
         b = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
         for x, y in zip(a, b):
@@ -164,7 +165,7 @@ def test_norms_entry_point_matches_update_norms():
         en = so.group_norms(rows, offs, mem, wmode="stale", staleness=st)
         drows = to_dev_rows(rows)
         us = star.UpdateStream(offs, mem, st)
-        for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AUTO):
+        for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AUTO, star.KERNEL_AFFINE_MFMA):
             star.star_set_kernel(kern)
             n = torch.full((U,), -1.0, device="cuda")
             star.star_group_norms(drows, us, n, wmode="stale")

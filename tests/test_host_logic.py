@@ -160,7 +160,7 @@ def test_noise_scale_host_function():
     assert lib.star_noise_scale(ctypes.c_int32(2), g, ctypes.c_double(0.0), None, None, None) == 4
     lib.star_group_gram.restype = ctypes.c_int
     ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
-    assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(17), ctypes.c_void_p(0x9000), None) == 2
+    assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(33), ctypes.c_void_p(0x9000), None) == 2
     assert lib.star_group_gram(ptrs, 0, ctypes.c_int64(8), ctypes.c_int32(4), None, None) == 1
 
 
