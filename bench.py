@@ -18,22 +18,25 @@ import time
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (each scaled by what
-# the same counter reads for a plain 1 GiB copy); valid only for the kernel source they were taken with.
+# the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip and
+# star_device.h, hashed together) they were taken with.
 MEASURED_TRAFFIC = {
-    "kernels_sha256": "e419062ed3682e02b449471470817de35dd50ebfdfb0da2db58fa7ab4e950402",
-    "bytes_per_launch": {"resnet50": 1226753237, "bert_base": 8801342833, "vgg16": 11068486191,
-                         "bert_large": 16321005021},
+    "kernels_sha256": "af695358187664d6872302623d0b2216fca082b21efdbc1efffd543299012962",
+    "bytes_per_launch": {"resnet50": 1226753166, "bert_base": 8801342684, "vgg16": 11068485174,
+                         "bert_large": 16320953411},
 }
 
 
 def measured_traffic(workload):
     import hashlib
-    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_09685_amd", "csrc", "star_kernels.hip")
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_09685_amd", "csrc")
+    h = hashlib.sha256()
     try:
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        for name in ("star_kernels.hip", "star_device.h"):
+            h.update(open(os.path.join(csrc, name), "rb").read())
     except OSError:
         return None
-    if digest != MEASURED_TRAFFIC["kernels_sha256"]:
+    if h.hexdigest() != MEASURED_TRAFFIC["kernels_sha256"]:
         return None            # the kernels changed since the counters were taken
     return MEASURED_TRAFFIC["bytes_per_launch"].get(workload)
 
@@ -47,7 +50,9 @@ def parse():
                     help="headline workload: tiny | resnet50 | bert_base | vgg16 | bert_large")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per-config table)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine"])
+    ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine", "affine_mfma"])
+    ap.add_argument("--norms", default="workload", choices=["workload", "on", "off"],
+                    help="per-group gradient norms: as the workload defines them (default), or forced on / off")
     ap.add_argument("--op", default="update", choices=["update", "publish", "reduce"],
                     help="update: star_group_update (the headline path); publish: the same with a bf16 copy of the "
                          "new params written in the pass; reduce: star_group_reduce, one full-group aggregation per call")
@@ -57,11 +62,16 @@ def parse():
     return ap.parse_args()
 
 
+FORCED_KERNEL = "auto"
+
+
 def kernel_label(star, wl, us):
     k, fs, fa = star.star_plan_choice(wl.W, us, lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay,
                                       wmode=wl.wmode, want_norms=wl.norms)
     dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
     if k == star.KERNEL_AFFINE:
+        if wl.norms and (wl.W > 16 or FORCED_KERNEL == "affine_mfma"):
+            return f"aff_mfma_kernel<{wl.W}, {dt}, update, {'wide' if wl.W > 16 else 'narrow'}>", fs, fa
         return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
     return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa
 
@@ -201,8 +211,14 @@ def main():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(1)
     star.load_library()
-    star.star_set_kernel({"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE}[a.kernel])
-    head_wl = workloads.WORKLOADS[a.workload]
+    global FORCED_KERNEL
+    FORCED_KERNEL = a.kernel
+    star.star_set_kernel({"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE,
+                          "affine_mfma": star.KERNEL_AFFINE_MFMA}[a.kernel])
+    import dataclasses
+    wl_of = {n: (w if a.norms == "workload" else dataclasses.replace(w, norms=a.norms == "on"))
+             for n, w in workloads.WORKLOADS.items()}
+    head_wl = wl_of[a.workload]
     if a.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -218,7 +234,7 @@ def main():
             if name == a.workload:
                 per_config.append(head)
             else:
-                per_config.append(measure(workloads.WORKLOADS[name], a.steps, a.warmup, torch, star, workloads, a.op))
+                per_config.append(measure(wl_of[name], a.steps, a.warmup, torch, star, workloads, a.op))
     out = {
         "metric": "group_updates_per_s" if a.op != "reduce" else "group_aggregations_per_s",
         "value": head["group_updates_per_s"],
@@ -234,7 +250,9 @@ def main():
             "bound": "hbm", "achieved": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "traffic": measured_traffic(a.workload) if a.op == "update" else None, "kernel": head["kernel"],
+            "traffic": (measured_traffic(a.workload)
+                        if a.op == "update" and a.norms == "workload" and a.kernel == "auto" else None),
+            "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "
                     "norm-finishing kernels that follow each update kernel",

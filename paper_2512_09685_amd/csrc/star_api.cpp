@@ -291,8 +291,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     hipError_t e = hipSuccess;
     int grid = 0;
     // collapsed update (with or without the Gram matrix)
-    if (route == star::Route::Affine || route == star::Route::AffinePlusDirectNorms) {
-        const bool gram = want_norms && route == star::Route::Affine;
+    if (route == star::Route::Affine) {
+        const bool gram = want_norms;
         if (update || gram) {
             star::AffArgs a;
             a.params = params;
@@ -330,9 +330,9 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             }
         }
     }
-    // step-by-step evaluation: everything (Seq), or only the norms after a collapsed update
-    if (route == star::Route::Seq || (route == star::Route::AffinePlusDirectNorms && want_norms)) {
-        const bool seq_update = update && route == star::Route::Seq;
+    // step-by-step evaluation
+    if (route == star::Route::Seq) {
+        const bool seq_update = update;
         const int umax = star::seq_max_updates(Wp, want_norms);
         for (int u0 = 0; u0 < U; u0 += umax) {
             const int n = std::min(umax, U - u0);

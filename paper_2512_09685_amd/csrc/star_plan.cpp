@@ -142,34 +142,20 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
 }
 
 Route choose_route(const Plan& plan, int grad_bytes, bool update, bool want_norms, int forced) {
-    const int Wc = plan.Wc;
-    const bool gram_ok = Wc <= kMaxGramW;
+    static_assert(STAR_MAX_WORKERS <= kMaxGramW, "every admissible row count has a Gram kernel");
     if (forced == STAR_KERNEL_SEQ) return Route::Seq;
-    if (forced == STAR_KERNEL_AFFINE || forced == STAR_KERNEL_AFFINE_MFMA) return (want_norms && !gram_ok) ? Route::AffinePlusDirectNorms : Route::Affine;
+    if (forced == STAR_KERNEL_AFFINE || forced == STAR_KERNEL_AFFINE_MFMA) return Route::Affine;
     // Two-term time model per element: HBM bytes at ~5 TB/s against fp32
     // multiply-adds at ~20 T/s sustained (about half of the unpacked vector
-    // peak); the larger term bounds a pass.
+    // peak); the larger term bounds a pass.  Without the update only the norms
+    // are computed: step-by-step without the step, or the Gram matrix alone.
     const double bw = 5.0e12, fma = 20.0e12;
-    const double row_bytes = (double)Wc * grad_bytes;
-    const double state_bytes = update ? 16.0 : 0.0;
-    auto pass = [&](double bytes, double fmas) { return std::max(bytes / bw, fmas / fma); };
-    const double t_seq = pass(row_bytes + state_bytes, plan.fma_seq);
-    if (!update) {  // norms only: direct (seq kernel without the step) or Gram
-        if (!gram_ok) return Route::Seq;
-        return pass(row_bytes, plan.fma_affine) < t_seq ? Route::Affine : Route::Seq;
-    }
-    double t_aff;
-    Route aff;
-    if (!want_norms || gram_ok) {
-        t_aff = pass(row_bytes + state_bytes, plan.fma_affine);
-        aff = Route::Affine;
-    } else {
-        double direct = 0;
-        for (int32_t y : plan.ysize) direct += y + 1;
-        t_aff = pass(row_bytes + state_bytes, 2.0 * Wc + 4.0) + pass(row_bytes, direct);
-        aff = Route::AffinePlusDirectNorms;
-    }
-    return t_aff < t_seq ? aff : Route::Seq;
+    const int Wc = plan.Wc;
+    const double bytes = (double)Wc * grad_bytes + (update ? 16.0 : 0.0);
+    (void)want_norms;   // already priced into fma_seq and fma_affine by build_plan
+    const double t_seq = std::max(bytes / bw, plan.fma_seq / fma);
+    const double t_aff = std::max(bytes / bw, plan.fma_affine / fma);
+    return t_aff < t_seq ? Route::Affine : Route::Seq;
 }
 
 }  // namespace star

@@ -49,7 +49,7 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
 constexpr int kMaxValuGramW = 16;
 constexpr int kMaxGramW = 32;
 
-enum class Route { Seq, Affine, AffinePlusDirectNorms };
+enum class Route { Seq, Affine };
 
 // Picks the cheaper evaluation from a two-term time model (HBM bytes versus
 // fp32 multiply-adds per element).  `forced` is a star_kernel.
