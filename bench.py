@@ -70,7 +70,7 @@ def kernel_label(star, wl, us):
                                       wmode=wl.wmode, want_norms=wl.norms)
     dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
     if k == star.KERNEL_AFFINE:
-        if wl.norms and (wl.W > 16 or FORCED_KERNEL == "affine_mfma"):
+        if wl.norms and (wl.W > 16 or FORCED_KERNEL != "affine"):
             return f"aff_mfma_kernel<{wl.W}, {dt}, update, {'wide' if wl.W > 16 else 'narrow'}>", fs, fa
         return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
     return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa

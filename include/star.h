@@ -89,9 +89,10 @@ typedef enum {
 typedef enum {
     STAR_KERNEL_AUTO = 0,  /* pick by arithmetic cost                                          */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
-    STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1) */
-    STAR_KERNEL_AFFINE_MFMA = 3 /* the same, with the Gram matrix behind the norms formed on the matrix
-                                   cores also for 16 rows or fewer (beyond 16 rows it always is)      */
+    STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
+                               matrix behind the norms in vector registers up to 16 rows             */
+    STAR_KERNEL_AFFINE_MFMA = 3 /* the same map, the Gram matrix formed on the matrix cores for any number
+                                   of rows (what AUTO uses when it picks the collapsed evaluation)    */
 } star_kernel;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is

@@ -49,7 +49,7 @@ std::atomic<int> g_kernel_choice{initial_kernel_choice()};
 // ---------------------------------------------------------------- workspace
 // A ring of slots.  One call uses one slot: a pinned host staging buffer and a
 // device buffer for the tables, a device buffer for the per-block partial sums
-// and the reduced Gram matrix.  A slot's event is recorded after the last
+// and the reduced Gram matrix, and the 16-byte tile queue.  A slot's event is recorded after the last
 // kernel that touches it; the slot is handed out again only once that event
 // has completed, so calls on different streams never share live memory.
 struct Slot {
@@ -59,6 +59,7 @@ struct Slot {
     size_t table_cap = 0;
     double* partials = nullptr;
     size_t partial_cap = 0;   // doubles
+    star::TileQueue* queue = nullptr;   // work queue of the slot's launches, zero whenever no kernel is running
     hipEvent_t done = nullptr;
     bool pending = false;     // `done` has been recorded after work that uses this slot
 };
@@ -96,11 +97,16 @@ void free_slot(Slot& s) {
     if (s.host) (void)hipHostFree(s.host);
     if (s.dev) (void)hipFree(s.dev);
     if (s.partials) (void)hipFree(s.partials);
+    if (s.queue) (void)hipFree(s.queue);
     s = Slot();
 }
 
 // Grows one slot to the asked capacities (its previous work has completed).
 star_status grow_slot(Slot& s, size_t table_bytes, size_t partial_doubles) {
+    if (!s.queue) {
+        STAR_HIP(hipMalloc(reinterpret_cast<void**>(&s.queue), 256));
+        STAR_HIP(hipMemset(s.queue, 0, 256));
+    }
     if (table_bytes > s.table_cap) {
         if (s.host) STAR_HIP(hipHostFree(s.host));
         if (s.dev) STAR_HIP(hipFree(s.dev));
@@ -132,7 +138,7 @@ star_status acquire_slot(int device, size_t table_bytes, size_t partial_doubles,
     if (s.pending) STAR_HIP(hipEventSynchronize(s.done));
     s.pending = false;
     if (!s.done) STAR_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
-    const bool grows = table_bytes > s.table_cap || partial_doubles > s.partial_cap;
+    const bool grows = table_bytes > s.table_cap || partial_doubles > s.partial_cap || !s.queue;
     s.device = device;
     star_status st = grow_slot(s, table_bytes, partial_doubles);
     if (st != STAR_OK) return st;
@@ -254,7 +260,8 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
     // a workspace slot only when something has to live in it (tables, norm partials)
     const TableLayout lay = table_layout(U, Wp);
-    const bool need_slot = need_seq_tables || need_gram_coef || want_norms;
+    const bool want_queue = star::queue_pays(P);
+    const bool need_slot = need_seq_tables || need_gram_coef || want_norms || want_queue;
     std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
     Slot* slot = nullptr;
     if (need_slot) {
@@ -267,6 +274,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     char* h = slot ? static_cast<char*>(slot->host) : nullptr;
     char* d = slot ? static_cast<char*>(slot->dev) : nullptr;
     double* partials = slot ? slot->partials : nullptr;
+    star::TileQueue* queue = slot ? slot->queue : nullptr;
     if (need_seq_tables) {
         float* c32 = reinterpret_cast<float*>(h + lay.coef32);
         float* l32 = reinterpret_cast<float*>(h + lay.lr32);
@@ -314,8 +322,9 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish = update ? publish : nullptr;
             a.publish_dtype = publish_dtype;
             a.partials = partials;
-            // Gram matrix on the vector ALUs up to 16 rows, on the matrix cores beyond (or when asked for)
-            const bool mfma = gram && (Wp > star::kMaxValuGramW || g_kernel_choice.load() == STAR_KERNEL_AFFINE_MFMA);
+            a.queue = queue;
+            // Gram matrix on the matrix cores; in vector registers only when that kernel is asked for (<= 16 rows)
+            const bool mfma = gram && (Wp > star::kMaxValuGramW || g_kernel_choice.load() != STAR_KERNEL_AFFINE);
             e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
                      : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
@@ -352,6 +361,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish = (seq_update && u0 + n == U) ? publish : nullptr;   // the last launch holds the final params
             a.publish_dtype = publish_dtype;
             a.partials = partials;
+            a.queue = queue;
             e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");
             if (want_norms) {
@@ -447,6 +457,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         a.vec_ok = vec_ok ? 1 : 0;
         a.norms = want_norms ? 1 : 0;
         a.partials = slot->partials;
+        a.queue = slot->queue;
         int grid = 0;
         hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
         if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
@@ -520,9 +531,10 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     a.P = P;
     a.vec_ok = vec_ok ? 1 : 0;
     a.partials = slot->partials;
+    a.queue = slot->queue;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
-    const bool mfma = Wp > star::kMaxValuGramW || g_kernel_choice.load() == STAR_KERNEL_AFFINE_MFMA;
+    const bool mfma = Wp > star::kMaxValuGramW || g_kernel_choice.load() != STAR_KERNEL_AFFINE;
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, (int)grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");
@@ -604,7 +616,7 @@ size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U) {
     const int Wp = star::padded_rows(W);
     const int grid_cap = star::kGridCap;
     return std::max<size_t>(table_layout(U, Wp).total, 64 * 1024) +
-           sizeof(double) * partial_doubles_needed(Wp, U, grid_cap);
+           sizeof(double) * partial_doubles_needed(Wp, U, grid_cap) + 256 /* tile queue */;
 }
 
 const char* star_last_error(void) { return g_err.c_str(); }

@@ -143,6 +143,41 @@ __device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
     return s;
 }
 
+// Dynamic order: the workgroups of a launch take tiles 0, 1, 2, ... from a queue, `claim` consecutive
+// tiles at a time, and call body(tile) for each (the whole workgroup together; body may synchronise).
+// Compared with a fixed assignment this keeps the tiles in flight a dense, slowly advancing window
+// even though compute units progress at different rates, and it balances the end of the kernel.
+// The next claim is requested before the current one is worked on, so the atomic's latency (several
+// microseconds when 256 workgroups share one counter) is hidden.  Every workgroup leaves after its
+// first claim beyond the last tile, so the loop ends for any queue state; the last one to leave
+// puts the queue back to zero.
+template <class Body>
+__device__ __forceinline__ void for_each_claimed_tile(TileQueue* __restrict__ q, const int64_t ntile, const int claim,
+                                                      Body&& body) {
+    __shared__ unsigned long long s_first;
+    unsigned long long nxt = 0;
+    if (threadIdx.x == 0) nxt = atomicAdd(&q->next, (unsigned long long)claim);
+    for (;;) {
+        if (threadIdx.x == 0) s_first = nxt;
+        __syncthreads();
+        const int64_t t0 = (int64_t)s_first;
+        __syncthreads();   // everyone has read s_first before thread 0 writes it again
+        if (t0 >= ntile) break;
+        if (threadIdx.x == 0) nxt = atomicAdd(&q->next, (unsigned long long)claim);
+        const int64_t t1 = t0 + claim < ntile ? t0 + claim : ntile;
+        for (int64_t t = t0; t < t1; ++t) body(t);
+    }
+    if (threadIdx.x == 0) {
+        // this workgroup's claims have all returned (their values were used above), so when the
+        // count reaches the grid size nobody touches `next` any more
+        const unsigned int left = atomicAdd(&q->done, 1u);
+        if (left + 1 == gridDim.x) {
+            atomicExch(&q->next, 0ull);
+            atomicExch(&q->done, 0u);
+        }
+    }
+}
+
 // ---------------------------------------------------------------- the collapsed update of one element
 constexpr int kGramFold = 64;  // tiles between folds of the pairwise-product accumulators (power of two)
 
@@ -166,6 +201,7 @@ __device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W]
 // Launch geometry: G workgroups per span, K tiles per workgroup, and the grid.
 struct Geometry {
     int grid, span_g, span_k;
+    int claim;   // > 0: tiles come from the queue, this many per claim; span_g / span_k then serve the ragged end only
 };
 
 // items = chunks (or single elements when the buffers are not 16-byte aligned).
@@ -183,6 +219,7 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
     const int64_t items = vec_ok ? std::max<int64_t>(P / vec, P % vec) : P;
     const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
     Geometry g;
+    g.claim = 0;
     if (reduces) {
         const int wg_bytes = std::max(1, thread_bytes) * kBlock;
         const int bpc = std::max(1, std::min(max_per_cu, (64 * 1024 + wg_bytes - 1) / wg_bytes));
@@ -195,6 +232,15 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
         g.span_k = (int)((tiles + max_grid - 1) / max_grid);   // 1 unless the shard is absurdly long
         g.grid = (int)((tiles + g.span_k - 1) / g.span_k);
     }
+    return g;
+}
+
+// Geometry of a launch that takes its tiles from a queue: `per_cu` long-lived workgroups per compute unit.
+inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu) {
+    Geometry g;
+    g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));
+    g.span_k = 0x7fffffff;
+    g.claim = kClaim;
     return g;
 }
 

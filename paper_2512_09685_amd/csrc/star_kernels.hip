@@ -45,7 +45,8 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
-                                                     double* __restrict__ partials) {
+                                                     double* __restrict__ partials, TileQueue* __restrict__ queue,
+                                                     const int claim) {
     constexpr int VEC = R::VEC;
     constexpr int NG = W * (W + 1) / 2;
     float acc[GRAM ? NG : 1];
@@ -65,17 +66,8 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
     const Span span = make_span(span_g, span_k);
     const int64_t nchunk = vec_ok ? P / VEC : 0;
 
-    int64_t c = span.first;
-    for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
-        if constexpr (GRAM) {
-            if ((k & (kGramFold - 1)) == kGramFold - 1) {
-#pragma unroll
-                for (int e = 0; e < NG; ++e) {
-                    fold[e * kBlock + threadIdx.x] += acc[e];
-                    acc[e] = 0.0f;
-                }
-            }
-        }
+    // one chunk: VEC elements of every row, the update, the pairwise products
+    auto process = [&](const int64_t c) {
         typename R::vec g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = R::load(rows.p[w], c);
@@ -111,6 +103,34 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
                 store_state(vq, momentum, c * (VEC / 4) + q);
                 if (publish) publish_chunk(pq, publish, publish_bf16, c * (VEC / 4) + q);
             }
+        }
+    };
+    bool queued = false;
+    if constexpr (!GRAM) {
+        // without the register-heavy Gram accumulators the kernel affords a second copy of the chunk
+        // code: tiles from the queue for long shards, a fixed assignment for short ones
+        if (claim > 0) {
+            queued = true;
+            const int64_t ntile = (nchunk + kBlock - 1) / kBlock;
+            for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
+                const int64_t c = tile * kBlock + threadIdx.x;
+                if (c < nchunk) process(c);
+            });
+        }
+    }
+    if (!queued) {
+        int64_t c = span.first;
+        for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
+            if constexpr (GRAM) {
+                if ((k & (kGramFold - 1)) == kGramFold - 1) {
+#pragma unroll
+                    for (int e = 0; e < NG; ++e) {
+                        fold[e * kBlock + threadIdx.x] += acc[e];
+                        acc[e] = 0.0f;
+                    }
+                }
+            }
+            process(c);
         }
     }
     // elements not covered by whole chunks (the ragged end, or everything when
@@ -391,10 +411,15 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
 template <int W, class R, bool UPDATE, bool GRAM>
 hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
-    const Geometry g = pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
+    // long shards without the Gram accumulators: one long-lived workgroup per compute unit, tiles from the
+    // queue (fewer waves in flight measured faster than more: 1 > 2 > 3 > 4 workgroups per unit)
+    const bool queued = !GRAM && a.queue && a.vec_ok && queue_pays(a.P);
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, 1)
+                              : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
-                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials);
+                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue,
+                       g.claim);
     return hipGetLastError();
 }
 

@@ -77,7 +77,8 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
                                                           const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                           const int vec_ok, const int span_g, const int span_k,
                                                           void* __restrict__ publish, const int publish_bf16,
-                                                          double* __restrict__ partials) {
+                                                          double* __restrict__ partials,
+                                                          TileQueue* __restrict__ queue, const int claim) {
     typedef GramTile<WIDE> GT;
     typedef typename GT::acc_t acc_t;
     typedef typename R::vec vec_t;
@@ -161,8 +162,8 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
         }
     };
 
-    // Tiles are walked with wave-uniform control flow (the matrix instructions need every lane);
-    // a lane beyond the end of the shard contributes zeros.
+    // Tiles come from the queue and are walked with wave-uniform control flow (the matrix instructions
+    // need every lane); a lane beyond the end of the shard contributes zeros.
     const int64_t first_tile = (int64_t)(blockIdx.x / span_g) * span_g * (int64_t)span_k + (blockIdx.x % span_g);
     const int64_t nchunk = vec_ok ? P / 4 : 0;
     const int64_t ntile = (nchunk + kBlock - 1) / kBlock;
@@ -198,9 +199,8 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
             for (int w = 0; w < W; ++w) g[w] = vec_t{};
         }
     };
-    int64_t tile = first_tile;
-    for (int k = 0; k < span_k && tile < ntile; ++k, tile += span_g) {
-        const int64_t c = tile * kBlock + threadIdx.x;
+    for_each_claimed_tile(queue, ntile, claim, [&](const int64_t t) {
+        const int64_t c = t * kBlock + threadIdx.x;
         vec_t g[W];
         f32x4 pq = {0, 0, 0, 0}, vq = {0, 0, 0, 0};
         fetch(c, g, pq, vq);
@@ -209,12 +209,12 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
         }
         gram_tile(g);
         fold();
-    }
+    });
     // elements not covered by whole chunks (the ragged end, or everything when some buffer is not
     // 16-byte aligned): one element per lane, same arithmetic
     const int64_t nrest = P - nchunk * 4;
     const int64_t nrtile = (nrest + kBlock - 1) / kBlock;
-    tile = first_tile;
+    int64_t tile = first_tile;
     for (int k = 0; k < span_k && tile < nrtile; ++k, tile += span_g) {
         const int64_t r = tile * kBlock + threadIdx.x;
         vec_t g[W];
@@ -267,13 +267,14 @@ namespace {
 template <int W, class R, bool UPDATE, bool WIDE>
 hipError_t launch_mfma_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_mfma_kernel<W, R, UPDATE, WIDE>;
-    // long-lived workgroups, stacked on a compute unit by the bytes a workgroup keeps in flight, as far
-    // as the LDS panels allow (33 KB each narrow, 66 KB wide, of 160 KB)
-    const int thread_bytes = W * 4 * (int)(std::is_same<R, RowBf16x4>::value ? 2 : 4) + (UPDATE ? 32 : 0);
-    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, true, num_cu, grid_cap, thread_bytes, WIDE ? 2 : 4);
+    // two long-lived workgroups per compute unit (one measured 15 % slower, three and four 3-10 %), tiles from
+    // the queue; the LDS panels (33 KB narrow, 66 KB wide per workgroup) allow that many
+    if (!a.queue) return hipErrorInvalidValue;
+    const Geometry g = queue_geometry(num_cu, grid_cap, 2);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
-                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials);
+                       g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue,
+                       g.claim);
     return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def test_gram_matrix(dtype, W, P, mfma):
     rows = rand_rows(rng, W, P, dtype)
     ref = so.gram(rows)
     out = torch.full((W, W), -1.0, dtype=torch.float64, device="cuda")
-    star.star_set_kernel(star.KERNEL_AFFINE_MFMA if mfma else star.KERNEL_AUTO)
+    star.star_set_kernel(star.KERNEL_AFFINE_MFMA if mfma else star.KERNEL_AFFINE)   # matrix cores / vector registers
     try:
         star.star_group_gram(to_dev_rows(rows), out)
         torch.cuda.synchronize()
