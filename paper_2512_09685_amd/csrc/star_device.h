@@ -236,6 +236,12 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
 }
 
 // Geometry of a launch that takes its tiles from a queue: `per_cu` long-lived workgroups per compute unit.
+// Measured on MI355X, fewer waves in flight are faster as long as they keep enough bytes in flight: kernels
+// that read-modify-write the state want one workgroup per unit from about 128 bytes per thread and tile
+// (1 > 2 > 3 > 4 by 2-4 % each step), lighter ones and the read-mostly aggregation want two.
+inline int queue_workgroups_per_cu(int thread_bytes, bool writes_state) {
+    return writes_state && thread_bytes >= 128 ? 1 : 2;
+}
 inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu) {
     Geometry g;
     g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));

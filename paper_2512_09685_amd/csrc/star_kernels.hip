@@ -213,8 +213,8 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const float mu, const float wd, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
-                                                     double* __restrict__ partials,
-                                                     const InlineTables inl) {
+                                                     double* __restrict__ partials, TileQueue* __restrict__ queue,
+                                                     const int claim, const InlineTables inl) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
     extern __shared__ float lds[];
     float* s_coef = lds;
@@ -242,8 +242,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
     const Span span = make_span(span_g, span_k);
     const int64_t nchunk = vec_ok ? P / 4 : 0;
 
-    int64_t c = span.first;
-    for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
+    auto process = [&](const int64_t c) {
         typename R::vec raw[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) raw[w] = R::load(rows.p[w], c);
@@ -277,6 +276,16 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
             store_state(vv, momentum, c);
             if (publish) publish_chunk(pv, publish, publish_bf16, c);
         }
+    };
+    if (claim > 0) {   // tiles from the queue
+        const int64_t ntile = (nchunk + kBlock - 1) / kBlock;
+        for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
+            const int64_t c = tile * kBlock + threadIdx.x;
+            if (c < nchunk) process(c);
+        });
+    } else {
+        int64_t c = span.first;
+        for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) process(c);
     }
     const int64_t nrest = P - nchunk * 4;
     int64_t r = span.first;
@@ -399,22 +408,26 @@ template <int W, class R, bool UPDATE, bool NORMS>
 hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = seq_kernel<W, R, UPDATE, NORMS>;
     const size_t lds = seq_lds_bytes(W, a.U, NORMS);
-    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap,
-                                     W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0), 4);
+    // short streams are bound by memory and take their tiles from the queue; long ones are bound by
+    // arithmetic and keep the fixed assignment with as many waves as fit
+    const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
+    const bool queued = a.queue && a.vec_ok && queue_pays(a.P) && a.U <= 4;
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE))
+                              : pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap, thread_bytes, 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
                        a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,
-                       a.partials, a.coef ? InlineTables() : *a.inl);
+                       a.partials, a.queue, g.claim, a.coef ? InlineTables() : *a.inl);
     return hipGetLastError();
 }
 
 template <int W, class R, bool UPDATE, bool GRAM>
 hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
-    // long shards without the Gram accumulators: one long-lived workgroup per compute unit, tiles from the
-    // queue (fewer waves in flight measured faster than more: 1 > 2 > 3 > 4 workgroups per unit)
+    // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
+    const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
     const bool queued = !GRAM && a.queue && a.vec_ok && queue_pays(a.P);
-    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, 1)
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE))
                               : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,

@@ -20,7 +20,9 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
                                                              void* const* __restrict__ t_out, const int U,
                                                              const int out_bf16, const int64_t P, const int vec_ok,
                                                              const int norms, const int span_g, const int span_k,
-                                                             double* __restrict__ partials, const InlineTables inl) {
+                                                             double* __restrict__ partials,
+                                                             TileQueue* __restrict__ queue, const int claim,
+                                                             const InlineTables inl) {
     extern __shared__ uint64_t lds64[];
     uint64_t* s_out = lds64;
     float* s_coef = reinterpret_cast<float*>(s_out + U);
@@ -73,8 +75,7 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
         }
     };
 
-    int64_t c = span.first;
-    for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
+    auto process = [&](const int64_t c) {
         typename R::vec raw[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) raw[w] = R::load(rows.p[w], c);
@@ -90,6 +91,16 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
             const f32x4 x = {gb[0], gb[1], gb[2], gb[3]};
             publish_chunk(x, out, out_bf16, c);
         });
+    };
+    if (claim > 0) {   // tiles from the queue
+        const int64_t ntile = (nchunk + kBlock - 1) / kBlock;
+        for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
+            const int64_t c = tile * kBlock + threadIdx.x;
+            if (c < nchunk) process(c);
+        });
+    } else {
+        int64_t c = span.first;
+        for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) process(c);
     }
     const int64_t nrest = P - nchunk * 4;
     int64_t r = span.first;
@@ -133,12 +144,14 @@ template <int W, class R>
 hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = reduce_rows_kernel<W, R>;
     const size_t lds = reduce_lds_bytes(W, a.U, a.norms != 0);
-    const Geometry g = pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
-                                     W * (int)sizeof(typename R::vec), 4);
+    const bool queued = a.queue && a.vec_ok && queue_pays(a.P);
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(0, false))
+                              : pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
+                                              W * (int)sizeof(typename R::vec), 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.rows, a.coef, a.mask, a.out, a.U,
                        a.out_dtype == STAR_BF16 ? 1 : 0, a.P, a.vec_ok, a.norms, g.span_g, g.span_k, a.partials,
-                       a.coef ? InlineTables() : *a.inl);
+                       a.queue, g.claim, a.coef ? InlineTables() : *a.inl);
     return hipGetLastError();
 }
 
