@@ -178,6 +178,52 @@ __device__ __forceinline__ void for_each_claimed_tile(TileQueue* __restrict__ q,
     }
 }
 
+// The same order with one tile of look-ahead, for kernels that issue the loads of the following tile
+// before they work on the current one: body(tile, following) with following < 0 at the end.  The
+// start of the next claim is made known to the whole workgroup when it begins the last tile of the
+// current claim, so the look-ahead also crosses claims.
+template <class Body>
+__device__ __forceinline__ void for_each_claimed_tile_ahead(TileQueue* __restrict__ q, const int64_t ntile,
+                                                            const int claim, Body&& body) {
+    __shared__ unsigned long long s_first;
+    unsigned long long nxt = 0;
+    if (threadIdx.x == 0) s_first = atomicAdd(&q->next, (unsigned long long)claim);
+    __syncthreads();
+    int64_t cur = (int64_t)s_first;
+    __syncthreads();
+    if (cur < ntile) {
+        if (threadIdx.x == 0) nxt = atomicAdd(&q->next, (unsigned long long)claim);
+        int64_t end = cur + claim < ntile ? cur + claim : ntile;
+        for (;;) {
+            int64_t following = cur + 1;
+            if (following >= end) {   // last tile of this claim: where does the next one start?
+                if (threadIdx.x == 0) s_first = nxt;
+                __syncthreads();
+                following = (int64_t)s_first;
+                __syncthreads();
+                if (following < ntile) {
+                    // no claim is requested once the end is known: nothing may touch the queue
+                    // after this workgroup has reported that it left
+                    if (threadIdx.x == 0) nxt = atomicAdd(&q->next, (unsigned long long)claim);
+                    end = following + claim < ntile ? following + claim : ntile;
+                } else {
+                    following = -1;
+                }
+            }
+            body(cur, following);
+            if (following < 0) break;
+            cur = following;
+        }
+    }
+    if (threadIdx.x == 0) {
+        const unsigned int left = atomicAdd(&q->done, 1u);
+        if (left + 1 == gridDim.x) {
+            atomicExch(&q->next, 0ull);
+            atomicExch(&q->done, 0u);
+        }
+    }
+}
+
 // ---------------------------------------------------------------- the collapsed update of one element
 constexpr int kGramFold = 64;  // tiles between folds of the pairwise-product accumulators (power of two)
 

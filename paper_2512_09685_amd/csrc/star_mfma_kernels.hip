@@ -199,17 +199,44 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
             for (int w = 0; w < W; ++w) g[w] = vec_t{};
         }
     };
-    for_each_claimed_tile(queue, ntile, claim, [&](const int64_t t) {
-        const int64_t c = t * kBlock + threadIdx.x;
-        vec_t g[W];
-        f32x4 pq = {0, 0, 0, 0}, vq = {0, 0, 0, 0};
-        fetch(c, g, pq, vq);
-        if constexpr (UPDATE) {
-            if (c < nchunk) update_chunk(c, g, pq, vq);
-        }
-        gram_tile(g);
-        fold();
-    });
+    // The loads of the following tile are issued before this tile's update and Gram work where the Gram
+    // phase is long enough to matter (not with 16 bf16 rows: 128 cycles a tile, and looking ahead measured
+    // 2 % slower there) and the rows of two tiles fit in registers (up to 256 bytes per thread and tile).
+    constexpr bool kAhead = sizeof(vec_t) * W <= 256 && (!BF || WIDE);
+    if constexpr (kAhead) {
+        vec_t gn[W];
+        f32x4 pn = {0, 0, 0, 0}, vn = {0, 0, 0, 0};
+        bool primed = false;
+        for_each_claimed_tile_ahead(queue, ntile, claim, [&](const int64_t t, const int64_t following) {
+            const int64_t c = t * kBlock + threadIdx.x;
+            if (!primed) {
+                fetch(c, gn, pn, vn);
+                primed = true;
+            }
+            vec_t g[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) g[w] = gn[w];
+            const f32x4 pq = pn, vq = vn;
+            if (following >= 0) fetch(following * kBlock + threadIdx.x, gn, pn, vn);
+            if constexpr (UPDATE) {
+                if (c < nchunk) update_chunk(c, g, pq, vq);
+            }
+            gram_tile(g);
+            fold();
+        });
+    } else {
+        for_each_claimed_tile(queue, ntile, claim, [&](const int64_t t) {
+            const int64_t c = t * kBlock + threadIdx.x;
+            vec_t g[W];
+            f32x4 pq = {0, 0, 0, 0}, vq = {0, 0, 0, 0};
+            fetch(c, g, pq, vq);
+            if constexpr (UPDATE) {
+                if (c < nchunk) update_chunk(c, g, pq, vq);
+            }
+            gram_tile(g);
+            fold();
+        });
+    }
     // elements not covered by whole chunks (the ragged end, or everything when some buffer is not
     // 16-byte aligned): one element per lane, same arithmetic
     const int64_t nrest = P - nchunk * 4;
@@ -267,10 +294,14 @@ namespace {
 template <int W, class R, bool UPDATE, bool WIDE>
 hipError_t launch_mfma_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_mfma_kernel<W, R, UPDATE, WIDE>;
-    // two long-lived workgroups per compute unit (one measured 15 % slower, three and four 3-10 %), tiles from
-    // the queue; the LDS panels (33 KB narrow, 66 KB wide per workgroup) allow that many
+    // Long-lived workgroups, tiles from the queue.  Two per compute unit, so that one wave's Gram phase overlaps
+    // another's loads; one where a single workgroup already keeps 64 KB and more in flight and looks a tile
+    // ahead (16 fp32 rows: 1.51 against 1.56 ms on the 110 M shard).  The LDS panels (33 KB narrow, 66 KB
+    // wide per workgroup) allow both.
+    constexpr int kRowBytes = W * (int)sizeof(typename R::vec);
+    const int per_cu = (!WIDE && kRowBytes >= 256) ? 1 : 2;
     if (!a.queue) return hipErrorInvalidValue;
-    const Geometry g = queue_geometry(num_cu, grid_cap, 2);
+    const Geometry g = queue_geometry(num_cu, grid_cap, per_cu);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
                        g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue,
