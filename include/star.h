@@ -282,6 +282,19 @@ star_status star_select_mode_ar(int32_t N, const double *iter_time, const double
  * environment variable STAR_KERNEL=auto|seq|affine|affine_mfma sets the initial value). */
 star_status star_set_kernel(int32_t kernel);
 
+/*
+ * How the workgroups of a kernel get their tiles (a tile is 1024 consecutive
+ * elements of every buffer).  Shards of at least `elements` elements are
+ * processed by one or two long-lived workgroups per compute unit that claim
+ * tiles in address order from a small work queue in the workspace; shorter
+ * shards get a fixed assignment, which starts faster.  Both compute the same
+ * values; the matrix-core Gram kernel always uses the queue.  Default 16 Mi
+ * (restored by elements = 0); 1 sends every shard through the queue, which is
+ * what the tests do to check that path on small inputs.  STAR_ERR_SHAPE for a
+ * negative value.
+ */
+star_status star_set_queue_threshold(int64_t elements);
+
 /* Bytes of internal device workspace one call of this shape uses. */
 size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U);
 

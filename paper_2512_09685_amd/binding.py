@@ -70,6 +70,8 @@ def load_library():
     lib.star_plan_choice.argtypes = [i32, vp, vp, i32, vp, vp, vp]
     lib.star_set_kernel.restype = ctypes.c_int
     lib.star_set_kernel.argtypes = [i32]
+    lib.star_set_queue_threshold.restype = ctypes.c_int
+    lib.star_set_queue_threshold.argtypes = [ctypes.c_int64]
     lib.star_workspace_bytes.restype = ctypes.c_size_t
     lib.star_workspace_bytes.argtypes = [i64, i32, i32]
     lib.star_last_error.restype = ctypes.c_char_p
@@ -323,6 +325,10 @@ def star_select_mode_ar(iter_time, child_time, phi: float, batch_total: float, w
 
 def star_set_kernel(kernel: int) -> None:
     _check(load_library().star_set_kernel(kernel))
+
+
+def star_set_queue_threshold(elements: int) -> None:
+    _check(load_library().star_set_queue_threshold(elements))
 
 
 def star_workspace_bytes(P: int, W: int, U: int) -> int:

@@ -45,6 +45,7 @@ int initial_kernel_choice() {
 }
 
 std::atomic<int> g_kernel_choice{initial_kernel_choice()};
+std::atomic<int64_t> g_queue_min{star::kQueueMinElements};
 
 // ---------------------------------------------------------------- workspace
 // A ring of slots.  One call uses one slot: a pinned host staging buffer and a
@@ -260,7 +261,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
     // a workspace slot only when something has to live in it (tables, norm partials)
     const TableLayout lay = table_layout(U, Wp);
-    const bool want_queue = star::queue_pays(P);
+    const bool want_queue = P >= g_queue_min.load();
     const bool need_slot = need_seq_tables || need_gram_coef || want_norms || want_queue;
     std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
     Slot* slot = nullptr;
@@ -322,9 +323,10 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish = update ? publish : nullptr;
             a.publish_dtype = publish_dtype;
             a.partials = partials;
-            a.queue = queue;
+            a.queue = want_queue ? queue : nullptr;
             // Gram matrix on the matrix cores; in vector registers only when that kernel is asked for (<= 16 rows)
             const bool mfma = gram && (Wp > star::kMaxValuGramW || g_kernel_choice.load() != STAR_KERNEL_AFFINE);
+            if (mfma) a.queue = queue;   // that kernel always takes its tiles from the queue
             e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
                      : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the collapsed update kernel");
@@ -361,7 +363,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish = (seq_update && u0 + n == U) ? publish : nullptr;   // the last launch holds the final params
             a.publish_dtype = publish_dtype;
             a.partials = partials;
-            a.queue = queue;
+            a.queue = want_queue ? queue : nullptr;
             e = star::launch_seq(Wp, grad_dtype, seq_update, want_norms, a, num_cu, grid_cap, &grid, stream);
             if (e != hipSuccess) return hip_fail(e, "launch of the step-by-step kernel");
             if (want_norms) {
@@ -457,7 +459,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         a.vec_ok = vec_ok ? 1 : 0;
         a.norms = want_norms ? 1 : 0;
         a.partials = slot->partials;
-        a.queue = slot->queue;
+        a.queue = P >= g_queue_min.load() ? slot->queue : nullptr;
         int grid = 0;
         hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
         if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
@@ -599,6 +601,13 @@ star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hpar
     if (kernel_out) *kernel_out = r == star::Route::Seq ? STAR_KERNEL_SEQ : STAR_KERNEL_AFFINE;
     if (fma_seq) *fma_seq = plan.fma_seq;
     if (fma_affine) *fma_affine = plan.fma_affine;
+    return STAR_OK;
+}
+
+star_status star_set_queue_threshold(int64_t elements) {
+    g_err.clear();
+    if (elements < 0) return set_err(STAR_ERR_SHAPE, "the threshold is negative");
+    g_queue_min.store(elements == 0 ? star::kQueueMinElements : elements);
     return STAR_OK;
 }
 

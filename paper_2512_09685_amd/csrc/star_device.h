@@ -119,6 +119,27 @@ __device__ __forceinline__ float wave_sum_to_lane63(float x) {
     return x;
 }
 
+// The same in double (each move is done on the two halves of the value).  The norm sums take this
+// one: which tiles a workgroup gets from the queue differs from run to run, and only sums that are
+// carried in double from the per-tile level on come out the same in fp32 every time.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_take(double x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, ROW_MASK, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+__device__ __forceinline__ double wave_sum_to_lane63(double x) {
+    x += dpp_take<0xB1, 0xf>(x);
+    x += dpp_take<0x4E, 0xf>(x);
+    x += dpp_take<0x141, 0xf>(x);
+    x += dpp_take<0x140, 0xf>(x);
+    x += dpp_take<0x142, 0xa>(x);
+    x += dpp_take<0x143, 0xc>(x);
+    return x;
+}
+
 // ---------------------------------------------------------------- compile-time loops
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {

@@ -30,7 +30,6 @@ constexpr int kClaim = 3;
 // per workgroup the claims' round trips show (1 Mi elements: 15 against 7.5 us); from 16 Mi on the
 // queue order wins (+12 % with 8 fp32 rows).
 constexpr int64_t kQueueMinElements = 16 << 20;
-inline bool queue_pays(int64_t P) { return P >= kQueueMinElements; }
 
 struct RowPtrs {
     const void* p[STAR_MAX_WORKERS];
@@ -77,7 +76,7 @@ struct SeqArgs {
     void* publish;         // device copy of the new params (P elements), or null
     int32_t publish_dtype; // star_dtype of that copy
     double* partials;      // device [U][grid] sums of gbar^2 per block (norms only)
-    TileQueue* queue;      // device, zeroed; null: static mapping of workgroups to tiles
+    TileQueue* queue;      // device, zeroed; null: fixed assignment of tiles to workgroups
 };
 
 // Largest number of updates one launch of the step-by-step kernel accepts
@@ -99,7 +98,7 @@ struct AffArgs {
     void* publish;          // device copy of the new params (P elements), or null
     int32_t publish_dtype;  // star_dtype of that copy
     double* partials;  // device [Wp(Wp+1)/2][grid] pairwise-product sums per block (gram only)
-    TileQueue* queue;  // device, zeroed; null: static mapping of workgroups to tiles
+    TileQueue* queue;  // device, zeroed; null: fixed assignment of tiles to workgroups (not for the matrix-core kernel)
 };
 
 // Collapsed evaluation, optionally accumulating the Gram matrix of the rows.
@@ -137,7 +136,7 @@ struct ReduceArgs {
     int32_t vec_ok;          // every row and every output 16-byte aligned
     int32_t norms;           // also accumulate sum of squares per group
     double* partials;        // device [U][grid] (norms only)
-    TileQueue* queue;        // device, zeroed; null: static mapping of workgroups to tiles
+    TileQueue* queue;        // device, zeroed; null: fixed assignment of tiles to workgroups
 };
 
 int reduce_max_updates(int Wp, bool norms);

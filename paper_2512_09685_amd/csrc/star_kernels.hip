@@ -171,11 +171,14 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
 }
 
 // ================================================================= step-by-step kernel
-// LDS: coef[U][W] | lr[U] | mask[U] | (norms) wave_part[4][U] | nacc[U][kBlock]
+// LDS: (norms) nacc[U][kBlock] | wave_part[4][U], both double | coef[U][W] | lr[U] | mask[U]
+// nacc holds one running sum of gbar^2 per thread and update.  It is double because the tiles a
+// thread sees depend on the queue: each chunk's fp32 sum of four squares is formed in a fixed order,
+// and added in double the order of the chunks matters only at 1e-16.
 template <int W, bool UPDATE, bool NORMS>
 __device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float (&v)[4],
                                           const float* s_coef, const float* s_lr, const uint32_t* s_mask,
-                                          float* s_nacc, const int U, const float mu, const float wd) {
+                                          double* s_nacc, const int U, const float mu, const float wd) {
     for (int u = 0; u < U; ++u) {
         const uint32_t m = __builtin_amdgcn_readfirstlane(s_mask[u]);
         float gb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -191,7 +194,7 @@ __device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float
             float s = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) s = __builtin_fmaf(gb[k], gb[k], s);  // unused slots hold 0
-            s_nacc[u * kBlock + threadIdx.x] += s;
+            s_nacc[u * kBlock + threadIdx.x] += (double)s;
         }
         if constexpr (UPDATE) {
             const float lr = s_lr[u];
@@ -216,12 +219,12 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      double* __restrict__ partials, TileQueue* __restrict__ queue,
                                                      const int claim, const InlineTables inl) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
-    extern __shared__ float lds[];
-    float* s_coef = lds;
+    extern __shared__ double lds[];
+    double* s_nacc = lds;
+    double* s_wave = s_nacc + (NORMS ? U * kBlock : 0);
+    float* s_coef = reinterpret_cast<float*>(s_wave + (NORMS ? (kBlock / 64) * U : 0));
     float* s_lr = s_coef + U * W;
     uint32_t* s_mask = reinterpret_cast<uint32_t*>(s_lr + U);
-    float* s_wave = reinterpret_cast<float*>(s_mask + U);
-    float* s_nacc = s_wave + (NORMS ? (kBlock / 64) * U : 0);
     if (t_coef) {
         for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
         for (int i = threadIdx.x; i < U; i += kBlock) {
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
         }
     }
     if constexpr (NORMS)
-        for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
+        for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0;
     __syncthreads();
 
     const Span span = make_span(span_g, span_k);
@@ -313,14 +316,14 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
     if constexpr (NORMS) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         for (int u = 0; u < U; ++u) {
-            const float s = wave_sum_to_lane63(s_nacc[u * kBlock + threadIdx.x]);
+            const double s = wave_sum_to_lane63(s_nacc[u * kBlock + threadIdx.x]);
             if (lane == 63) s_wave[wave * U + u] = s;
         }
         __syncthreads();
         for (int u = threadIdx.x; u < U; u += kBlock) {
             double s = 0.0;
 #pragma unroll
-            for (int q = 0; q < kBlock / 64; ++q) s += (double)s_wave[q * U + u];
+            for (int q = 0; q < kBlock / 64; ++q) s += s_wave[q * U + u];
             partials[(int64_t)u * gridDim.x + blockIdx.x] = s;
         }
     }
@@ -401,7 +404,8 @@ int padded_rows(int Wc) {
 namespace {
 
 size_t seq_lds_bytes(int W, int U, bool norms) {
-    return sizeof(float) * ((size_t)U * W + 2 * (size_t)U + (norms ? (size_t)(kBlock / 64) * U + (size_t)U * kBlock : 0));
+    return sizeof(float) * ((size_t)U * W + 2 * (size_t)U) +
+           (norms ? sizeof(double) * ((size_t)(kBlock / 64) * U + (size_t)U * kBlock) : 0);
 }
 
 template <int W, class R, bool UPDATE, bool NORMS>
@@ -411,7 +415,7 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
     // short streams are bound by memory and take their tiles from the queue; long ones are bound by
     // arithmetic and keep the fixed assignment with as many waves as fit
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = a.queue && a.vec_ok && queue_pays(a.P) && a.U <= 4;
+    const bool queued = a.queue && a.vec_ok && a.U <= 4;
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE))
                               : pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap, thread_bytes, 4);
     *grid_out = g.grid;
@@ -426,7 +430,7 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
     // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = !GRAM && a.queue && a.vec_ok && queue_pays(a.P);
+    const bool queued = !GRAM && a.queue && a.vec_ok;
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE))
                               : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     *grid_out = g.grid;

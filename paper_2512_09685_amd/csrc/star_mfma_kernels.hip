@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
     constexpr int NG = W * (W + 1) / 2;
     constexpr int kWaves = kBlock / 64;
     constexpr int kPanelBytes = N * kPanelRowBytes;
-    static_assert(kPanelBytes >= 64 * GT::REGS * 4, "the panel doubles as the reduction buffer");
+    static_assert(kPanelBytes >= 64 * GT::REGS * 8, "the panel doubles as the reduction buffer");
     __shared__ __align__(16) unsigned char panel[kWaves][kPanelBytes];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -97,13 +97,14 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
     for (int w = W; w < N; ++w) *reinterpret_cast<u32x2*>(T + w * kPanelRowBytes + 8 * lane) = u32x2{0u, 0u};
 
     // two accumulator sets used alternately, so that consecutive matrix instructions do not wait for
-    // each other's result; acc2 is the second-level sum (see fold)
-    acc_t acc, accb, acc2;
+    // each other's result; acc2 is the second-level sum, in double (see fold)
+    acc_t acc, accb;
+    double acc2[GT::REGS];
 #pragma unroll
     for (int r = 0; r < GT::REGS; ++r) {
         acc[r] = 0.0f;
         accb[r] = 0.0f;
-        acc2[r] = 0.0f;
+        acc2[r] = 0.0;
     }
     const unsigned char* const my_row = T + (lane % N) * kPanelRowBytes + 16 * (lane / N);
 
@@ -151,12 +152,16 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
         }
     };
     // After every tile the matrix-core accumulators (256 products each by then) are folded into a
-    // second set: long fp32 chains of products of short-mantissa (bf16) values drift low, about 1e-9
-    // per term, and a tile is the natural place to cut them; the fold is 4 or 16 additions per lane.
+    // second set kept in double.  Two reasons.  Long fp32 chains of products of short-mantissa (bf16)
+    // values drift low, about 1e-9 per term, and a tile is the natural place to cut them.  And which
+    // tiles a workgroup gets from the queue differs from run to run: a tile's own sums are formed in
+    // a fixed order, and adding those in double makes the order of the tiles matter only at 1e-16,
+    // far below the fp32 the norms are returned in, so that they come out the same every run.
+    // The fold is 4 or 16 additions per lane.
     auto fold = [&]() {
 #pragma unroll
         for (int r = 0; r < GT::REGS; ++r) {
-            acc2[r] += acc[r] + accb[r];
+            acc2[r] += (double)(acc[r] + accb[r]);
             acc[r] = 0.0f;
             accb[r] = 0.0f;
         }
@@ -270,9 +275,9 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
 
     // workgroup total of every Gamma entry, in double, one partial per workgroup; each wave's
     // accumulators go through its own (now idle) panel
-    float* const red = reinterpret_cast<float*>(T);
+    double* const red = reinterpret_cast<double*>(T);
 #pragma unroll
-    for (int r = 0; r < GT::REGS; ++r) red[lane * GT::REGS + r] = (acc[r] + accb[r]) + acc2[r];
+    for (int r = 0; r < GT::REGS; ++r) red[lane * GT::REGS + r] = (double)(acc[r] + accb[r]) + acc2[r];
     __syncthreads();
     for (int e = threadIdx.x; e < NG; e += kBlock) {
         int i = 0, rem = e;
@@ -284,7 +289,7 @@ __global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ pa
         const int src = GT::lane_of(i, j) * GT::REGS + GT::reg_of(i);
         double s = 0.0;
 #pragma unroll
-        for (int q = 0; q < kWaves; ++q) s += (double)reinterpret_cast<const float*>(panel[q])[src];
+        for (int q = 0; q < kWaves; ++q) s += reinterpret_cast<const double*>(panel[q])[src];
         partials[(int64_t)e * gridDim.x + blockIdx.x] = s;
     }
 }

@@ -24,11 +24,13 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
                                                              TileQueue* __restrict__ queue, const int claim,
                                                              const InlineTables inl) {
     extern __shared__ uint64_t lds64[];
+    // out pointers | (norms) running sums of gbar^2 per thread and group, and per wave, in double (the
+    // tiles a thread sees depend on the queue; see the step-by-step kernel) | coefficients | masks
     uint64_t* s_out = lds64;
-    float* s_coef = reinterpret_cast<float*>(s_out + U);
+    double* s_nacc = reinterpret_cast<double*>(s_out + U);
+    double* s_wave = s_nacc + (norms ? U * kBlock : 0);
+    float* s_coef = reinterpret_cast<float*>(s_wave + (norms ? (kBlock / 64) * U : 0));
     uint32_t* s_mask = reinterpret_cast<uint32_t*>(s_coef + U * W);
-    float* s_wave = reinterpret_cast<float*>(s_mask + U);
-    float* s_nacc = s_wave + (norms ? (kBlock / 64) * U : 0);
     if (t_coef) {
         for (int i = threadIdx.x; i < U * W; i += kBlock) s_coef[i] = t_coef[i];
         for (int i = threadIdx.x; i < U; i += kBlock) {
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
         }
     }
     if (norms)
-        for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0f;
+        for (int u = 0; u < U; ++u) s_nacc[u * kBlock + threadIdx.x] = 0.0;
     __syncthreads();
 
     const Span span = make_span(span_g, span_k);
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
                 float s = 0.0f;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) s = __builtin_fmaf(gb[k], gb[k], s);  // unused slots hold 0
-                s_nacc[u * kBlock + threadIdx.x] += s;
+                s_nacc[u * kBlock + threadIdx.x] += (double)s;
             }
             const uint64_t o = s_out[u];
             const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)o);
@@ -120,14 +122,14 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
     if (norms) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         for (int u = 0; u < U; ++u) {
-            const float s = wave_sum_to_lane63(s_nacc[u * kBlock + threadIdx.x]);
+            const double s = wave_sum_to_lane63(s_nacc[u * kBlock + threadIdx.x]);
             if (lane == 63) s_wave[wave * U + u] = s;
         }
         __syncthreads();
         for (int u = threadIdx.x; u < U; u += kBlock) {
             double s = 0.0;
 #pragma unroll
-            for (int q = 0; q < kBlock / 64; ++q) s += (double)s_wave[q * U + u];
+            for (int q = 0; q < kBlock / 64; ++q) s += s_wave[q * U + u];
             partials[(int64_t)u * gridDim.x + blockIdx.x] = s;
         }
     }
@@ -136,15 +138,15 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const RowPtrs rows,
 namespace {
 
 size_t reduce_lds_bytes(int W, int U, bool norms) {
-    return sizeof(uint64_t) * (size_t)U +
-           sizeof(float) * ((size_t)U * W + (size_t)U + (norms ? (size_t)(kBlock / 64) * U + (size_t)U * kBlock : 0));
+    return sizeof(uint64_t) * (size_t)U + sizeof(float) * ((size_t)U * W + (size_t)U) +
+           (norms ? sizeof(double) * ((size_t)(kBlock / 64) * U + (size_t)U * kBlock) : 0);
 }
 
 template <int W, class R>
 hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = reduce_rows_kernel<W, R>;
     const size_t lds = reduce_lds_bytes(W, a.U, a.norms != 0);
-    const bool queued = a.queue && a.vec_ok && queue_pays(a.P);
+    const bool queued = a.queue && a.vec_ok;
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(0, false))
                               : pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
                                               W * (int)sizeof(typename R::vec), 4);

@@ -1,11 +1,22 @@
 """Shared helpers of the GPU parity tests: move host inputs to the device, call
 the library through its binding, bring results back."""
 import numpy as np
+import pytest
 import torch
 
 import paper_2512_09685_amd as star
 
 TOL = {"f32": 1e-6, "bf16": 4e-3}   # max |x-ref| / (|ref| + RMS(ref)), per gradient dtype
+
+
+@pytest.fixture(autouse=True, params=["fixed", "queue"])
+def tile_order(request):
+    """Runs every test of a module that imports it twice: with the fixed assignment of tiles to
+    workgroups and with tiles claimed from the work queue (which the library itself only uses
+    from 16 Mi elements on), so that the small, fully checked cases cover both."""
+    star.star_set_queue_threshold(1 if request.param == "queue" else 1 << 62)
+    yield request.param
+    star.star_set_queue_threshold(0)
 
 
 def to_dev_rows(rows_np):

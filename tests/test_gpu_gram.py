@@ -6,7 +6,7 @@ import torch
 
 import paper_2512_09685_amd as star
 from oracle import star_oracle as so
-from gpu_util import rand_rows, to_dev_rows
+from gpu_util import rand_rows, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 

@@ -8,7 +8,7 @@ import torch
 import paper_2512_09685_amd as star
 import workloads
 from oracle import star_oracle as so
-from gpu_util import TOL, gpu_update, rand_rows, rand_stream, to_dev_rows
+from gpu_util import TOL, gpu_update, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -34,6 +34,9 @@ def check(p, v, n, ep, ev, en, dtype, what=""):
     (1, 1, 1, True), (2, 3, 2, False), (4, 5, 10, True), (3, 1023, 7, True), (5, 1025, 12, False),
     (8, 4099, 24, True), (16, 70001, 16, True), (17, 33333, 9, True), (32, 50000, 12, False),
     (32, 20003, 6, True), (12, 600011, 20, True),
+    # short streams (the step-by-step kernel is queue-ordered up to 4 updates) and shards of more tiles than
+    # the first, fixed round of claims covers (256 or 512 workgroups x 2 tiles on average)
+    (8, 300007, 2, True), (16, 1300003, 3, True), (16, 1300003, 16, True), (6, 1100000, 1, False),
 ])
 def test_random_shapes(dtype, kname, W, P, U, norms):
     rng = np.random.default_rng(1000 * W + U + (7 if dtype == "bf16" else 0))
@@ -91,18 +94,22 @@ def test_member_order_is_bitwise_irrelevant():
 
 
 def test_run_to_run_bitwise_reproducible():
+    """Params and momentum are the same bits every run.  So are the norms, also when the tiles come from
+    the queue and every run hands them to the workgroups differently: the sums across tiles are carried
+    in double, where that order shows only at 1e-16, far below the fp32 result."""
     rng = np.random.default_rng(6)
-    W, P, U = 16, 300001, 20
+    W, P = 16, 900001
     rows = rand_rows(rng, W, P, "bf16")
-    offs, mem, st = rand_stream(rng, W, U, stale=3)
     p0 = rng.standard_normal(P).astype(np.float32)
     v0 = np.zeros(P, np.float32)
     hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale", want_norms=True)
-    for k in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AFFINE_MFMA):
+    for k, U in ((star.KERNEL_SEQ, 3), (star.KERNEL_SEQ, 20), (star.KERNEL_AFFINE, 20), (star.KERNEL_AFFINE_MFMA, 20)):
+        offs, mem, st = rand_stream(rng, W, U, stale=3)
         a = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
-        b = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
-        for x, y in zip(a, b):
-            assert np.array_equal(x, y)
+        for _ in range(3):
+            b = gpu_update(p0, v0, rows, offs, mem, staleness=st, kernel=k, **hp)
+            for x, y in zip(a, b):
+                assert np.array_equal(x, y)
 
 
 def test_batch_split_carries_state():

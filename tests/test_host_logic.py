@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
     assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_group_gram",
-            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_set_kernel",
+            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_set_kernel", "star_set_queue_threshold",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
@@ -67,6 +67,9 @@ def test_set_kernel_validation():
     lib = star.load_library()
     assert lib.star_set_kernel(5) == 6
     assert lib.star_set_kernel(0) == 0
+    assert lib.star_set_queue_threshold(-1) == 2
+    assert lib.star_set_queue_threshold(1) == 0
+    assert lib.star_set_queue_threshold(0) == 0
 
 
 def _rand_stream(rng, W, U, stale=None):
