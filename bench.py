@@ -18,12 +18,12 @@ import time
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (each scaled by what
-# the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip and
-# star_device.h, hashed together) they were taken with.
+# the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip,
+# star_mfma_kernels.hip and star_device.h, hashed together) they were taken with.
 MEASURED_TRAFFIC = {
-    "kernels_sha256": "af695358187664d6872302623d0b2216fca082b21efdbc1efffd543299012962",
-    "bytes_per_launch": {"resnet50": 1226753166, "bert_base": 8801342684, "vgg16": 11068485174,
-                         "bert_large": 16320953411},
+    "kernels_sha256": "3b14de9cf49e3c31125f237b4ecec049cc2bdcfc5354124db23f6690147d12a1",
+    "bytes_per_launch": {"resnet50": 1227070866, "bert_base": 8802206023, "vgg16": 11069993716,
+                         "bert_large": 16325402015},
 }
 
 
@@ -32,7 +32,7 @@ def measured_traffic(workload):
     csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_09685_amd", "csrc")
     h = hashlib.sha256()
     try:
-        for name in ("star_kernels.hip", "star_device.h"):
+        for name in ("star_kernels.hip", "star_mfma_kernels.hip", "star_device.h"):
             h.update(open(os.path.join(csrc, name), "rb").read())
     except OSError:
         return None
