@@ -53,9 +53,10 @@ def parse():
     ap.add_argument("--kernel", default="auto", choices=["auto", "seq", "affine", "affine_mfma"])
     ap.add_argument("--norms", default="workload", choices=["workload", "on", "off"],
                     help="per-group gradient norms: as the workload defines them (default), or forced on / off")
-    ap.add_argument("--op", default="update", choices=["update", "publish", "reduce"],
+    ap.add_argument("--op", default="update", choices=["update", "publish", "reduce", "norms"],
                     help="update: star_group_update (the headline path); publish: the same with a bf16 copy of the "
-                         "new params written in the pass; reduce: star_group_reduce, one full-group aggregation per call")
+                         "new params written in the pass; reduce: star_group_reduce, one full-group aggregation per "
+                         "call; norms: star_group_norms alone (the rows are read, nothing is written)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, run three plain device copies of 1 GiB (a known-size kernel to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -89,7 +90,8 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     for c in range(wl.calls):
         s = workloads.make_update_stream(wl, 0, c)
         streams.append(star.UpdateStream(s["offsets"], s["members"], s["staleness"]))
-    norms = [torch.zeros(wl.U, device=dev) for _ in range(wl.calls)] if wl.norms else [None] * wl.calls
+    norms = ([torch.zeros(wl.U, device=dev) for _ in range(wl.calls)] if wl.norms or op == "norms"
+             else [None] * wl.calls)
     hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
     extra_bytes = 0
     if op == "publish":
@@ -109,6 +111,8 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
             elif op == "publish":
                 star.star_group_update_publish(p, v, sets[c % nsets], streams[c], pub, norms_out=norms[c],
                                                stream=stream, **hp)
+            elif op == "norms":
+                star.star_group_norms(sets[c % nsets], streams[c], norms[c], wmode=wl.wmode, stream=stream)
             else:
                 star.star_group_reduce(out, sets[c % nsets], full, norms_out=None if norms[c] is None else norms[c][:1],
                                        stream=stream)
@@ -141,6 +145,17 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         n_updates = 1
         label = f"reduce_rows_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>"
         fs, fa = float(wl.W + (1 if wl.norms else 0)), None
+    if op == "norms":
+        bytes_per_call = wl.P * len(used) * wl.grad_bytes                   # the referenced rows, read once
+        dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
+        k, fs, fa = star.star_plan_choice(wl.W, streams[0], lr=wl.lr, momentum_coef=wl.momentum,
+                                          weight_decay=wl.weight_decay, wmode=wl.wmode, want_norms=True)
+        if k == star.KERNEL_SEQ:
+            label = f"seq_kernel<{wl.W}, {dt}, norms only>"
+        elif FORCED_KERNEL == "affine" and wl.W <= 16:
+            label = f"aff_kernel<{wl.W}, {dt}, norms only, gram>"
+        else:
+            label = f"aff_mfma_kernel<{wl.W}, {dt}, norms only, {'wide' if wl.W > 16 else 'narrow'}>"
     bytes_per_step = bytes_per_call * wl.calls
     gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     res = {
