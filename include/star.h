@@ -295,6 +295,17 @@ star_status star_set_kernel(int32_t kernel);
  */
 star_status star_set_queue_threshold(int64_t elements);
 
+/*
+ * Host-only: the fixed first round of the work queue for a launch of
+ * `workgroups` workgroups.  Workgroup b starts on tiles first_tile[b] ..
+ * first_tile[b] + count[b] - 1 (counts cycle 1, 2, 3: unequal on purpose, so
+ * that the workgroups do not run in step); the tiles from *base on are handed
+ * out by the queue's counter, three at a time.  first_tile and count hold
+ * `workgroups` entries.  STAR_ERR_SHAPE for workgroups < 1, STAR_ERR_NULL for
+ * a NULL output.
+ */
+star_status star_plan_claims(int32_t workgroups, int64_t *first_tile, int32_t *count, int64_t *base);
+
 /* Bytes of internal device workspace one call of this shape uses. */
 size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U);
 

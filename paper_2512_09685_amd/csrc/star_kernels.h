@@ -31,6 +31,23 @@ constexpr int kClaim = 3;
 // queue order wins (+12 % with 8 fp32 rows).
 constexpr int64_t kQueueMinElements = 16 << 20;
 
+// First round of claims (see for_each_claimed_tile): workgroup b of G gets 1 + b % claim tiles, laid out
+// one after the other from tile 0; the queue's counter hands out the tiles from `base` on.
+struct FirstClaim {
+    int64_t t0;                // first tile of the workgroup's first claim
+    int n;                     // tiles in it
+    unsigned long long base;   // tiles covered by all first claims together
+};
+__host__ __device__ inline FirstClaim first_claim_of(const int64_t b, const int64_t G, const int claim) {
+    const int64_t per_group = (int64_t)claim * (claim + 1) / 2;   // tiles taken by `claim` consecutive workgroups
+    const int64_t r = b % claim, rg = G % claim;
+    FirstClaim f;
+    f.t0 = (b / claim) * per_group + r * (r + 1) / 2;
+    f.n = (int)r + 1;
+    f.base = (unsigned long long)((G / claim) * per_group + rg * (rg + 1) / 2);
+    return f;
+}
+
 struct RowPtrs {
     const void* p[STAR_MAX_WORKERS];
 };

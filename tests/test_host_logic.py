@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
     assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_group_gram",
-            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_set_kernel", "star_set_queue_threshold",
+            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_plan_claims", "star_set_kernel", "star_set_queue_threshold",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
@@ -70,6 +70,24 @@ def test_set_kernel_validation():
     assert lib.star_set_queue_threshold(-1) == 2
     assert lib.star_set_queue_threshold(1) == 0
     assert lib.star_set_queue_threshold(0) == 0
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 255, 256, 257, 512, 608, 1024])
+def test_first_round_of_claims_tiles_the_front_of_the_shard(G):
+    """The fixed first claims are disjoint, leave no gap, start at tile 0 and end where the counter
+    takes over; their sizes cycle 1, 2, 3 (unequal, so that workgroups do not run in step)."""
+    first, count, base = star.star_plan_claims(G)
+    assert count.tolist() == [1 + b % 3 for b in range(G)]
+    covered = np.zeros(base, np.int32)
+    for b in range(G):
+        covered[first[b]:first[b] + count[b]] += 1
+    assert first[0] == 0 and (covered == 1).all() and int(count.sum()) == base
+
+
+def test_plan_claims_validation():
+    lib = star.load_library()
+    assert lib.star_plan_claims(0, None, None, None) == 2
+    assert lib.star_plan_claims(4, None, None, None) == 1
 
 
 def _rand_stream(rng, W, U, stale=None):
