@@ -73,7 +73,7 @@ struct GramTile<true> {
 constexpr int kPanelRowBytes = 512 + 16;
 
 template <int W, class R, bool UPDATE, bool WIDE>
-__global__ __launch_bounds__(kBlock) void aff_mfma_kernel(float* __restrict__ params, float* __restrict__ momentum,
+__global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                           const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                           const int vec_ok, const int span_g, const int span_k,
                                                           void* __restrict__ publish, const int publish_bf16,
