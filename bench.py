@@ -57,6 +57,8 @@ def parse():
                     help="update: star_group_update (the headline path); publish: the same with a bf16 copy of the "
                          "new params written in the pass; reduce: star_group_reduce, one full-group aggregation per "
                          "call; norms: star_group_norms alone (the rows are read, nothing is written)")
+    ap.add_argument("--updates", type=int, default=0,
+                    help="updates per call instead of the workload's (1 = every gradient report applied on arrival)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, run three plain device copies of 1 GiB (a known-size kernel to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -233,6 +235,8 @@ def main():
     import dataclasses
     wl_of = {n: (w if a.norms == "workload" else dataclasses.replace(w, norms=a.norms == "on"))
              for n, w in workloads.WORKLOADS.items()}
+    if a.updates > 0:
+        wl_of = {n: dataclasses.replace(w, U=a.updates) for n, w in wl_of.items()}
     head_wl = wl_of[a.workload]
     if a.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -266,7 +270,8 @@ def main():
             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "traffic": (measured_traffic(a.workload)
-                        if a.op == "update" and a.norms == "workload" and a.kernel == "auto" else None),
+                        if a.op == "update" and a.norms == "workload" and a.kernel == "auto" and a.updates == 0
+                        else None),
             "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "

@@ -87,7 +87,7 @@ typedef enum {
 /* How the U updates are evaluated on the device (both give the same result up
  * to fp32 rounding; see star_plan_affine). */
 typedef enum {
-    STAR_KERNEL_AUTO = 0,  /* pick by arithmetic cost                                          */
+    STAR_KERNEL_AUTO = 0,  /* a single update: SEQ; two or more: AFFINE_MFMA                  */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
     STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
                                matrix behind the norms in vector registers up to 16 rows             */

@@ -412,10 +412,10 @@ template <int W, class R, bool UPDATE, bool NORMS>
 hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = seq_kernel<W, R, UPDATE, NORMS>;
     const size_t lds = seq_lds_bytes(W, a.U, NORMS);
-    // short streams are bound by memory and take their tiles from the queue; long ones are bound by
-    // arithmetic and keep the fixed assignment with as many waves as fit
+    // one or two updates are bound by memory and take their tiles from the queue; longer streams are bound
+    // by arithmetic and latency and keep the fixed assignment with as many waves as fit
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = a.queue && a.vec_ok && a.U <= 4;
+    const bool queued = a.queue && a.vec_ok && a.U <= 2;
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE))
                               : pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap, thread_bytes, 4);
     *grid_out = g.grid;

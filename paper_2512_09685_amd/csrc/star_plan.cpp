@@ -141,21 +141,18 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
     return STAR_OK;
 }
 
-Route choose_route(const Plan& plan, int grad_bytes, bool update, bool want_norms, int forced) {
+Route choose_route(const Plan& plan, int forced) {
     static_assert(STAR_MAX_WORKERS <= kMaxGramW, "every admissible row count has a Gram kernel");
     if (forced == STAR_KERNEL_SEQ) return Route::Seq;
     if (forced == STAR_KERNEL_AFFINE || forced == STAR_KERNEL_AFFINE_MFMA) return Route::Affine;
-    // Two-term time model per element: HBM bytes at ~5 TB/s against fp32
-    // multiply-adds at ~20 T/s sustained (about half of the unpacked vector
-    // peak); the larger term bounds a pass.  Without the update only the norms
-    // are computed: step-by-step without the step, or the Gram matrix alone.
-    const double bw = 5.0e12, fma = 20.0e12;
-    const int Wc = plan.Wc;
-    const double bytes = (double)Wc * grad_bytes + (update ? 16.0 : 0.0);
-    (void)want_norms;   // already priced into fma_seq and fma_affine by build_plan
-    const double t_seq = std::max(bytes / bw, plan.fma_seq / fma);
-    const double t_aff = std::max(bytes / bw, plan.fma_affine / fma);
-    return t_aff < t_seq ? Route::Affine : Route::Seq;
+    // A single update has nothing to collapse and the literal kernel does the least work for it (no Gram
+    // matrix behind the norm, one finishing kernel fewer).  From two updates on the collapsed form is
+    // never behind: both forms are bound by the same bytes, and the literal kernel's inner loop (LDS
+    // coefficient reads, a wave-uniform branch per row and update) stops hiding under the memory time
+    // at the low occupancy the large shards run best at -- measured 1.40 against 1.49 ms in its favour
+    // on 16 fp32 rows with two updates, but 12.4 against 9.6 ms on 16 bf16 rows, and behind everywhere
+    // from three updates on.
+    return plan.U <= 1 ? Route::Seq : Route::Affine;
 }
 
 }  // namespace star

@@ -51,8 +51,8 @@ constexpr int kMaxGramW = 32;
 
 enum class Route { Seq, Affine };
 
-// Picks the cheaper evaluation from a two-term time model (HBM bytes versus
-// fp32 multiply-adds per element).  `forced` is a star_kernel.
-Route choose_route(const Plan& plan, int grad_bytes, bool update, bool want_norms, int forced);
+// Picks the evaluation: the literal kernel for a single update, the collapsed
+// one from two updates on.  `forced` is a star_kernel.
+Route choose_route(const Plan& plan, int forced);
 
 }  // namespace star
