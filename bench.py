@@ -72,6 +72,8 @@ def kernel_label(star, wl, us):
     k, fs, fa = star.star_plan_choice(wl.W, us, lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay,
                                       wmode=wl.wmode, want_norms=wl.norms)
     dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
+    if wl.grad_dtype == "bf16" and FORCED_KERNEL != "seq":
+        k = star.KERNEL_AFFINE      # star_plan_choice answers for fp32 rows; bf16 rows never take the literal kernel
     if k == star.KERNEL_AFFINE:
         if wl.norms and (wl.W > 16 or FORCED_KERNEL != "affine"):
             return f"aff_mfma_kernel<{wl.W}, {dt}, update, {'wide' if wl.W > 16 else 'narrow'}>", fs, fa
@@ -136,10 +138,10 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     ms_per_step = ev_ms / steps
     assert bool(torch.isfinite(p[:: max(1, wl.P // 4096)]).all()), "non-finite parameters after the timed steps"
 
-    used = set()
-    for us in streams:
-        used |= set(int(x) for x in us.members)
-    bytes_per_call = wl.algorithmic_bytes_per_call(len(used)) + extra_bytes
+    # rows referenced per call (each call reads only the rows its own groups name), averaged over the calls
+    used = [set(int(x) for x in us.members) for us in streams]
+    n_used = sum(len(u) for u in used) / len(used)
+    bytes_per_call = int(sum(wl.algorithmic_bytes_per_call(len(u)) for u in used) / len(used)) + extra_bytes
     n_updates = wl.U
     label, fs, fa = kernel_label(star, wl, streams[0])
     if op == "reduce":
@@ -148,7 +150,7 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         label = f"reduce_rows_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>"
         fs, fa = float(wl.W + (1 if wl.norms else 0)), None
     if op == "norms":
-        bytes_per_call = wl.P * len(used) * wl.grad_bytes                   # the referenced rows, read once
+        bytes_per_call = int(wl.P * n_used * wl.grad_bytes)                 # the referenced rows, read once
         dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
         k, fs, fa = star.star_plan_choice(wl.W, streams[0], lr=wl.lr, momentum_coef=wl.momentum,
                                           weight_decay=wl.weight_decay, wmode=wl.wmode, want_norms=True)

@@ -87,7 +87,7 @@ typedef enum {
 /* How the U updates are evaluated on the device (both give the same result up
  * to fp32 rounding; see star_plan_affine). */
 typedef enum {
-    STAR_KERNEL_AUTO = 0,  /* a single update: SEQ; two or more: AFFINE_MFMA                  */
+    STAR_KERNEL_AUTO = 0,  /* a single update on fp32 rows: SEQ; otherwise AFFINE_MFMA        */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
     STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
                                matrix behind the norms in vector registers up to 16 rows             */
@@ -178,8 +178,8 @@ star_status star_group_reduce(void *const *out_rows, star_dtype out_dtype, const
 star_status star_plan_affine(int32_t W, const star_updates *upd, const star_hparams *hp, double M[4], double *B);
 
 /*
- * Host-only: which evaluation star_group_update would use for this stream
- * (STAR_KERNEL_SEQ or STAR_KERNEL_AFFINE), and optionally the fused
+ * Host-only: which evaluation star_group_update would use for this stream on
+ * fp32 rows (STAR_KERNEL_SEQ or STAR_KERNEL_AFFINE), and optionally the fused
  * multiply-adds per element of each (either pointer may be NULL).
  */
 star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hparams *hp, int32_t want_norms,

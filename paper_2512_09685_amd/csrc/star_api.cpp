@@ -234,7 +234,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     if (st != STAR_OK) return st;
     const int grid_cap = star::kGridCap;
 
-    const star::Route route = star::choose_route(plan, g_kernel_choice.load());
+    const star::Route route = star::choose_route(plan, grad_dtype == STAR_F32 ? 4 : 2, g_kernel_choice.load());
     const int Wp = star::padded_rows(Wc);
 
     // rows in compact order; padding rows repeat the last row with zero coefficients
@@ -596,7 +596,7 @@ star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hpar
     std::string msg;
     star_status st = star::build_plan(W, upd, hp, 0, want_norms != 0, &plan, &msg);
     if (st != STAR_OK) return set_err(st, msg);
-    const star::Route r = star::choose_route(plan, g_kernel_choice.load());
+    const star::Route r = star::choose_route(plan, 4, g_kernel_choice.load());
     if (kernel_out) *kernel_out = r == star::Route::Seq ? STAR_KERNEL_SEQ : STAR_KERNEL_AFFINE;
     if (fma_seq) *fma_seq = plan.fma_seq;
     if (fma_affine) *fma_affine = plan.fma_affine;

@@ -141,18 +141,19 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
     return STAR_OK;
 }
 
-Route choose_route(const Plan& plan, int forced) {
+Route choose_route(const Plan& plan, int grad_bytes, int forced) {
     static_assert(STAR_MAX_WORKERS <= kMaxGramW, "every admissible row count has a Gram kernel");
     if (forced == STAR_KERNEL_SEQ) return Route::Seq;
     if (forced == STAR_KERNEL_AFFINE || forced == STAR_KERNEL_AFFINE_MFMA) return Route::Affine;
-    // A single update has nothing to collapse and the literal kernel does the least work for it (no Gram
-    // matrix behind the norm, one finishing kernel fewer).  From two updates on the collapsed form is
-    // never behind: both forms are bound by the same bytes, and the literal kernel's inner loop (LDS
-    // coefficient reads, a wave-uniform branch per row and update) stops hiding under the memory time
-    // at the low occupancy the large shards run best at -- measured 1.40 against 1.49 ms in its favour
-    // on 16 fp32 rows with two updates, but 12.4 against 9.6 ms on 16 bf16 rows, and behind everywhere
-    // from three updates on.
-    return plan.U <= 1 ? Route::Seq : Route::Affine;
+    // A single update has nothing to collapse, and on fp32 rows the literal kernel does the least work for
+    // it (no Gram matrix behind the norm, one finishing kernel fewer: 0.82 against 0.95 ms on 110 M
+    // elements with the norm, the same time without).  On bf16 rows, and from two updates on, the
+    // collapsed form is ahead: both forms are bound by the same bytes, and the literal kernel's inner loop
+    // (LDS coefficient reads, a wave-uniform branch per row and update) stops hiding under the memory time
+    // at the low occupancy the large shards run best at -- a single update on bf16 rows 4 % behind, two
+    // updates 1.40 against 1.49 ms in its favour on 16 fp32 rows but 12.4 against 9.6 ms on 16 bf16 rows,
+    // behind everywhere from three updates on.
+    return (plan.U <= 1 && grad_bytes == 4) ? Route::Seq : Route::Affine;
 }
 
 }  // namespace star

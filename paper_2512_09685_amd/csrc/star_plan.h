@@ -51,8 +51,9 @@ constexpr int kMaxGramW = 32;
 
 enum class Route { Seq, Affine };
 
-// Picks the evaluation: the literal kernel for a single update, the collapsed
-// one from two updates on.  `forced` is a star_kernel.
-Route choose_route(const Plan& plan, int forced);
+// Picks the evaluation: the literal kernel for a single update on fp32 rows,
+// the collapsed one otherwise.  `grad_bytes` is the size of a gradient element,
+// `forced` a star_kernel.
+Route choose_route(const Plan& plan, int grad_bytes, int forced);
 
 }  // namespace star
