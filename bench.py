@@ -21,9 +21,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 # the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip,
 # star_mfma_kernels.hip and star_device.h, hashed together) they were taken with.
 MEASURED_TRAFFIC = {
-    "kernels_sha256": "33a5269bf6e3fa71cb953114836d741d36477d6ceb923c15cd1d9f502f43a030",
-    "bytes_per_launch": {"resnet50": 1227069586, "bert_base": 8802225976, "vgg16": 11069960673,
-                         "bert_large": 16325412892},
+    "kernels_sha256": "c6a96358097db4ec74d34e0db357e3594f13ca4d7d432aa58d5c6aebbfcd64d2",
+    "bytes_per_launch": {"resnet50": 1227071400, "bert_base": 8802256346, "vgg16": 11069986975,
+                         "bert_large": 16325367134},
 }
 
 
