@@ -44,8 +44,10 @@ def measured_traffic(workload):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps first; the step time keeps falling for the first 25-50 ms of sustained work "
+                         "(bert_base: 1.64 ms for the first step after a pause, 1.46 ms from about the 12th on)")
     ap.add_argument("--workload", default="bert_base",
                     help="headline workload: tiny | resnet50 | bert_base | vgg16 | bert_large")
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per-config table)")
@@ -127,15 +129,18 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     e0.record(stream)
-    for _ in range(steps):
+    for i in range(steps):
         step()
+        marks[i].record(stream)       # per-step times for the median / minimum; the headline is the whole region
     e1.record(stream)
     stream.synchronize()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = ev_ms / steps
+    per_step = sorted(a.elapsed_time(b) for a, b in zip([e0] + marks[:-1], marks))
     assert bool(torch.isfinite(p[:: max(1, wl.P // 4096)]).all()), "non-finite parameters after the timed steps"
 
     # rows referenced per call (each call reads only the rows its own groups name), averaged over the calls
@@ -167,6 +172,7 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         "grad_dtype": wl.grad_dtype, "norms": wl.norms,
         "group_updates_per_s": n_updates * wl.calls / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms / steps,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "algorithmic_bytes_per_step": bytes_per_step, "bytes_per_element": bytes_per_call / wl.P,
         "hbm_gbps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "kernel": label,
         "fma_per_element_seq": fs, "fma_per_element_affine": fa,
@@ -262,6 +268,7 @@ def main():
         "unit": "group-updates/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": head["ms_per_step"],
+        "ms_per_step_median": head["ms_per_step_median"], "ms_per_step_min": head["ms_per_step_min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": a.workload, "op": a.op, "P": head_wl.P, "W": head_wl.W, "U": head_wl.U * head_wl.calls,

@@ -155,11 +155,11 @@ struct Span {
     int64_t first, step;
     int32_t K;
 };
-__device__ __forceinline__ Span make_span(const int span_g, const int span_k) {
+__device__ __forceinline__ Span make_span(const int span_g, const int span_k, const int threads = kBlock) {
     const int64_t G = span_g;
     Span s;
-    s.first = ((int64_t)(blockIdx.x / span_g) * G * span_k + (blockIdx.x % span_g)) * kBlock + threadIdx.x;
-    s.step = G * kBlock;
+    s.first = ((int64_t)(blockIdx.x / span_g) * G * span_k + (blockIdx.x % span_g)) * threads + threadIdx.x;
+    s.step = G * threads;
     s.K = span_k;
     return s;
 }
@@ -280,6 +280,7 @@ __device__ __forceinline__ void aff_step(float& p, float& v, const float (&g)[W]
 struct Geometry {
     int grid, span_g, span_k;
     int claim;   // > 0: tiles come from the queue, this many per claim; span_g / span_k then serve the ragged end only
+    int threads; // workgroup size (kBlock unless a launcher says otherwise)
 };
 
 // items = chunks (or single elements when the buffers are not 16-byte aligned).
@@ -298,6 +299,7 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
     const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
     Geometry g;
     g.claim = 0;
+    g.threads = kBlock;
     if (reduces) {
         const int wg_bytes = std::max(1, thread_bytes) * kBlock;
         const int bpc = std::max(1, std::min(max_per_cu, (64 * 1024 + wg_bytes - 1) / wg_bytes));
@@ -322,6 +324,7 @@ inline int queue_workgroups_per_cu(int thread_bytes, bool writes_state) {
 }
 inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu) {
     Geometry g;
+    g.threads = kBlock;
     g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));
     g.span_k = 0x7fffffff;
     g.claim = kClaim;
