@@ -21,9 +21,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 # the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip,
 # star_mfma_kernels.hip and star_device.h, hashed together) they were taken with.
 MEASURED_TRAFFIC = {
-    "kernels_sha256": "c6a96358097db4ec74d34e0db357e3594f13ca4d7d432aa58d5c6aebbfcd64d2",
-    "bytes_per_launch": {"resnet50": 1227071400, "bert_base": 8802256346, "vgg16": 11069986975,
-                         "bert_large": 16325367134},
+    "kernels_sha256": "2c6c93965161fc6499191d5da6158ec01f0f0fd46b9645b459e137ff56cfc967",
+    "bytes_per_launch": {"resnet50": 1227058745, "bert_base": 8802195463, "vgg16": 11071416082,
+                         "bert_large": 16325424933},
 }
 
 
