@@ -283,13 +283,10 @@ struct Geometry {
     int threads; // workgroup size (kBlock unless a launcher says otherwise)
 };
 
-// items = chunks (or single elements when the buffers are not 16-byte aligned).
-// A kernel that ends with a per-workgroup norm reduction runs one long-lived
-// workgroup per compute unit, all sweeping the shard as a single span; the
-// others get one tile per workgroup, dispatched in address order.  Both keep
-// the set of addresses in flight a narrow window that advances through every
-// row together, which is what measured fastest on MI355X for this mix of 16+
-// read streams and two read-modify-write streams.
+// Fixed assignment of tiles (short shards, launches without a queue).  items = chunks (or single
+// elements when the buffers are not 16-byte aligned).  A kernel that ends with a per-workgroup norm
+// reduction runs long-lived workgroups that sweep the shard as a single span; the others get one
+// tile per workgroup, dispatched in address order.
 // `thread_bytes`: bytes one thread has in flight per tile; long-lived workgroups are stacked on a compute unit
 // (up to `max_per_cu`) until about 64 KB per unit are in flight, which light bf16 kernels need and heavy fp32
 // ones already have with one workgroup.
