@@ -5,7 +5,9 @@ A step is one pass of the whole path over one batch of synthetic input: all
 calls of the workload (one star_group_update with U updates; four back-to-back
 calls for the streamed BERT-large workload), gradient norms included where the
 workload asks for them.  Inputs are resident in HBM before the timed region.
-Prints ONE JSON line.
+Before the W warm-up steps the same calls run untimed for 80 ms ("wake-up": the
+device's step times settle only after 25-50 ms of sustained work); then exactly
+K steps are timed.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only]
 """
@@ -16,6 +18,7 @@ import sys
 import time
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+WAKEUP_SECONDS = 0.08    # untimed work before the warm-up steps, see measure()
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (each scaled by what
 # the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip,
@@ -133,6 +136,13 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
                 star.star_group_reduce(out, sets[c % nsets], full, norms_out=None if norms[c] is None else norms[c][:1],
                                        stream=stream)
 
+    # Wake-up: after a pause the device needs 25-50 ms of sustained work before step times settle (the first
+    # steps run 10-30 % slower), whatever --warmup says; untimed, like the warm-up steps that follow.
+    t_wake, n_wake = time.perf_counter(), 0
+    while time.perf_counter() - t_wake < WAKEUP_SECONDS:
+        step()
+        stream.synchronize()
+        n_wake += 1
     for _ in range(warmup):
         step()
     stream.synchronize()
@@ -183,6 +193,7 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         "group_updates_per_s": n_updates * wl.calls / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms / steps,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "wakeup_steps": n_wake,
         "algorithmic_bytes_per_step": bytes_per_step, "bytes_per_element": bytes_per_call / wl.P,
         "hbm_gbps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "kernel": label,
         "fma_per_element_seq": fs, "fma_per_element_affine": fa,
