@@ -150,3 +150,49 @@ def test_full_size_publish_and_reduce(name):
     else:
         ref = float(torch.linalg.vector_norm(out[0].float().double()).item())
     assert abs(n.item() / ref - 1) <= (1e-5 if wl.W <= 16 else 2e-3)
+
+
+@pytest.mark.parametrize("name", ["bert_base", "bert_large"])
+def test_full_size_single_update(name):
+    """One update per call at full size (every gradient report applied on arrival): fp32 rows take the
+    step-by-step kernel in queue order, bf16 rows the collapsed one.  State on sampled elements, the
+    one norm against the oracle over the whole shard."""
+    wl = workloads.WORKLOADS[name]
+    rng = np.random.default_rng(77)
+    idx = sample_indices(wl.P, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    p = workloads.make_params(wl, 0, "cuda")
+    v = workloads.make_momentum(wl, "cuda")
+    rows = workloads.make_grad_rows(wl, 0, 0, "cuda")
+    s = workloads.make_update_stream(wl, 0, 0)
+    hi = int(s["offsets"][1])
+    offs = np.array([0, hi], np.int32)
+    mem = np.asarray(s["members"][:hi], np.int32)
+    st = None if s["staleness"] is None else np.asarray(s["staleness"][:hi], np.int32)
+    print(f"full-size single update {name}: P={wl.P} group of {hi} of {wl.W} workers", flush=True)
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    tol = TOL[wl.grad_dtype]
+    ep, ev = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
+    norms = torch.zeros(1, device="cuda")
+    for call in range(2):                                   # twice: the second call starts from the first's state
+        star.star_group_update(p, v, rows, star.UpdateStream(offs, mem, st), norms_out=norms, **hp)
+        torch.cuda.synchronize()
+        ep, ev, _ = so.group_update(ep, ev, rows_at(rows, idx_dev), offs, mem, staleness=st, **hp)
+        assert so.max_rel_err(p[idx_dev].cpu().numpy(), ep) <= tol
+        assert so.max_rel_err(v[idx_dev].cpu().numpy(), ev) <= tol
+    host_rows = []
+    first = None
+    for w in range(wl.W):
+        if w in set(int(m) for m in mem):
+            x = rows[w].cpu()
+            host_rows.append(x.view(torch.int16).numpy().view(np.uint16) if x.dtype == torch.bfloat16 else x.numpy())
+            first = host_rows[-1] if first is None else first
+        else:
+            host_rows.append(None)
+    host_rows = [r if r is not None else first for r in host_rows]     # rows outside the group are never read
+    en = so.group_norms(host_rows, offs, mem, wmode=wl.wmode, staleness=st)
+    e_n = abs(float(norms.cpu().numpy()[0]) - float(en[0])) / float(en[0])
+    print(f"  norm vs oracle over the whole shard: {e_n:.3g}", flush=True)
+    assert e_n <= min(tol, 2e-6)
+    del p, v, rows, host_rows
+    torch.cuda.empty_cache()
