@@ -29,7 +29,11 @@
  * Arithmetic on the device is fp32 with fused multiply-add, members summed in
  * ascending worker id; gradients may be fp32 or bf16 (widened exactly to
  * fp32).  Results do not depend on the order in which a group lists its
- * members and are bitwise reproducible from run to run.
+ * members.  Params and momentum are bitwise reproducible from run to run.
+ * The norms are accumulated in fp32 within a tile of 1024 elements, in a
+ * fixed order, and in double from there on; on long shards the tiles reach
+ * the workgroups in a different order on every run, which moves the double
+ * sums at the 1e-16 level and leaves the fp32 results the same.
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory of the current device, "host"
@@ -49,8 +53,9 @@
  *     16-byte aligned the vector path is used, otherwise an element-wise path
  *     with the same arithmetic (identical results).
  *   - The library keeps a small internal workspace (coefficient tables,
- *     per-block norm partials), created on first use, released by
- *     star_shutdown().  Calls may come from several host threads.
+ *     per-block norm partials, a 16-byte work queue per slot), created on
+ *     first use, released by star_shutdown().  Calls may come from several
+ *     host threads.
  */
 #ifndef STAR_H
 #define STAR_H
