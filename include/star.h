@@ -33,7 +33,8 @@
  * The norms are accumulated in fp32 within a tile of 1024 elements, in a
  * fixed order, and in double from there on; on long shards the tiles reach
  * the workgroups in a different order on every run, which moves the double
- * sums at the 1e-16 level and leaves the fp32 results the same.
+ * sums at the 1e-16 level; the fp32 results change only if a sum lies that
+ * close to a rounding boundary of fp32 (about once in 1e9 values).
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory of the current device, "host"
