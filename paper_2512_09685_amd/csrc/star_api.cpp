@@ -56,6 +56,7 @@ std::atomic<int64_t> g_queue_min{star::kQueueMinElements};
 struct Slot {
     int device = -1;
     void* host = nullptr;     // pinned
+    void* host_dev = nullptr; // the same memory as the device addresses it
     void* dev = nullptr;      // tables
     size_t table_cap = 0;
     double* partials = nullptr;
@@ -111,10 +112,11 @@ star_status grow_slot(Slot& s, size_t table_bytes, size_t partial_doubles) {
     if (table_bytes > s.table_cap) {
         if (s.host) STAR_HIP(hipHostFree(s.host));
         if (s.dev) STAR_HIP(hipFree(s.dev));
-        s.host = s.dev = nullptr;
+        s.host = s.host_dev = s.dev = nullptr;
         s.table_cap = 0;
         const size_t cap = std::max<size_t>(table_bytes, 64 * 1024);
         STAR_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        STAR_HIP(hipHostGetDevicePointer(&s.host_dev, s.host, 0));
         STAR_HIP(hipMalloc(&s.dev, cap));
         s.table_cap = cap;
     }
@@ -290,11 +292,13 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
         for (int u = 0; u < U; ++u)
             for (int k = 0; k < Wp; ++k) c64[(size_t)u * Wp + k] = k < Wc ? plan.coef[(size_t)u * Wc + k] : 0.0;
     }
-    if (need_seq_tables || need_gram_coef) {
-        const size_t lo = need_seq_tables ? 0 : lay.coef64;
-        const size_t hi = need_gram_coef ? lay.total : lay.coef64;
-        STAR_HIP(hipMemcpyAsync(d + lo, h + lo, hi - lo, hipMemcpyHostToDevice, stream));
-    }
+    // The step-by-step tables are read by every workgroup and are copied to the device.  The Gram
+    // coefficients (a few KB, read once, by the one small kernel that ends the call) are read where they
+    // are, in the slot's pinned host buffer: no copy engine in the stream.
+    if (need_seq_tables) STAR_HIP(hipMemcpyAsync(d, h, lay.coef64, hipMemcpyHostToDevice, stream));
+    const double* gram_coef = (slot && slot->host_dev)
+                                  ? reinterpret_cast<const double*>(static_cast<char*>(slot->host_dev) + lay.coef64)
+                                  : nullptr;
 
     hipError_t e = hipSuccess;
     int grid = 0;
@@ -334,8 +338,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
                 double* gamma = partials + (size_t)ng * grid;
                 e = star::launch_reduce(partials, ng, grid, gamma, nullptr, stream);
                 if (e != hipSuccess) return hip_fail(e, "launch of the Gram reduction");
-                e = star::launch_gram_norms(gamma, reinterpret_cast<const double*>(d + lay.coef64), U, Wp, norms_out,
-                                            stream);
+                e = star::launch_gram_norms(gamma, gram_coef, U, Wp, norms_out, stream);
                 if (e != hipSuccess) return hip_fail(e, "launch of the norm kernel");
             }
         }
