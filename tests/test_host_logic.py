@@ -210,3 +210,43 @@ def test_affine_map_property_random_streams():
         np.testing.assert_allclose(x[1], v, rtol=0, atol=1e-11)
 
     prop()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_kernel_digest_ignores_comments_only():
+    """bench.py keeps rocprofv3's measured HBM bytes together with a digest of the kernel sources and
+    reports them only while the digest matches: it must move with the code and not with comments."""
+    import importlib
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    bench = importlib.import_module("bench")
+    real_open = open
+    edits = {}
+
+    def fake_open(path, mode="r", *a, **k):
+        f = real_open(path, mode, *a, **k)
+        if str(path).endswith("star_device.h") and "b" not in mode and edits:
+            import io
+            text = f.read()
+            f.close()
+            return io.StringIO(edits["fn"](text))
+        return f
+
+    base = bench.kernel_source_digest()
+    import builtins
+    try:
+        builtins.open = fake_open
+        edits["fn"] = lambda t: t.replace("namespace star {", "// a remark\nnamespace star {   /* another */", 1)
+        assert bench.kernel_source_digest() == base
+        edits["fn"] = lambda t: t.replace("constexpr int kGramFold = 64;", "constexpr int kGramFold = 32;", 1)
+        assert bench.kernel_source_digest() != base
+    finally:
+        builtins.open = real_open
