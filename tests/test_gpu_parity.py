@@ -347,3 +347,41 @@ def test_very_long_stream():
     ep, ev, en = so.group_update(p0, v0, rows, offs, mem, **hp)
     p, v, n = gpu_update(p0, v0, rows, offs, mem, **hp)
     check(p, v, n, ep, ev, en, "f32", "U=5000")
+
+
+def test_interleaved_shards_shapes_and_kernels_without_host_sync():
+    """24 calls on two streams, cycling through three shards of different length, row count, dtype and
+    update count (so that consecutive launches differ in kernel, grid size and workgroup size), with no
+    host synchronisation in between.  Every shard's final state and last norms must match the oracle
+    applied to the same sequence: the workspace slots and their work queues are reused many times."""
+    rng = np.random.default_rng(2024)
+    specs = [(16, 200003, "f32", 9), (28, 150001, "bf16", 5), (6, 333337, "f32", 1)]
+    shards = []
+    for W, P, dtype, U in specs:
+        rows = rand_rows(rng, W, P, dtype)
+        p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+        shards.append(dict(W=W, P=P, dtype=dtype, U=U, rows=rows, dev=to_dev_rows(rows),
+                           p=torch.from_numpy(p0).cuda(), v=torch.zeros(P, device="cuda"), ep=p0, ev=np.zeros(P, np.float32),
+                           n=torch.zeros(U, device="cuda"), en=None))
+    hp = dict(lr=0.02, momentum_coef=0.9, weight_decay=1e-4, wmode="stale")
+    s = [torch.cuda.Stream(), torch.cuda.Stream()]
+    calls = []
+    for k in range(24):
+        sh = shards[k % 3]
+        offs, mem, st = rand_stream(rng, sh["W"], sh["U"], stale=3)
+        calls.append((k % 3, offs, mem, st))
+    torch.cuda.synchronize()
+    for k, (i, offs, mem, st) in enumerate(calls):
+        sh = shards[i]
+        # a shard always uses the same stream, so its calls stay ordered; the two streams overlap
+        star.star_group_update(sh["p"], sh["v"], sh["dev"], star.UpdateStream(offs, mem, st), norms_out=sh["n"],
+                               stream=s[i % 2], **hp)
+    for x in s:
+        x.synchronize()
+    for i, offs, mem, st in calls:
+        sh = shards[i]
+        sh["ep"], sh["ev"], sh["en"] = so.group_update(sh["ep"], sh["ev"], sh["rows"], offs, mem, staleness=st,
+                                                      want_norms=True, **hp)
+    for sh in shards:
+        check(sh["p"].cpu().numpy(), sh["v"].cpu().numpy(), sh["n"].cpu().numpy(), sh["ep"], sh["ev"], sh["en"],
+              sh["dtype"], f"interleaved W={sh['W']} {sh['dtype']}")
