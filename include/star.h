@@ -303,14 +303,17 @@ star_status star_set_queue_threshold(int64_t elements);
 
 /*
  * Host-only: the fixed first round of the work queue for a launch of
- * `workgroups` workgroups.  Workgroup b starts on tiles first_tile[b] ..
- * first_tile[b] + count[b] - 1 (counts cycle 1, 2, 3: unequal on purpose, so
- * that the workgroups do not run in step); the tiles from *base on are handed
- * out by the queue's counter, three at a time.  first_tile and count hold
- * `workgroups` entries.  STAR_ERR_SHAPE for workgroups < 1, STAR_ERR_NULL for
+ * `workgroups` workgroups that claim `tiles_per_claim` tiles at a time (the
+ * kernels use 3, or 5 when a thread moves less than 96 bytes per tile).
+ * Workgroup b starts on tiles first_tile[b] .. first_tile[b] + count[b] - 1
+ * (counts cycle 1, 2, .., tiles_per_claim: unequal on purpose, so that the
+ * workgroups do not run in step); the tiles from *base on are handed out by
+ * the queue's counter.  first_tile and count hold `workgroups` entries.
+ * STAR_ERR_SHAPE for workgroups < 1 or tiles_per_claim < 1, STAR_ERR_NULL for
  * a NULL output.
  */
-star_status star_plan_claims(int32_t workgroups, int64_t *first_tile, int32_t *count, int64_t *base);
+star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_t *first_tile, int32_t *count,
+                             int64_t *base);
 
 /* Bytes of internal device workspace one call of this shape uses. */
 size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U);

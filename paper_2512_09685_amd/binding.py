@@ -71,7 +71,7 @@ def load_library():
     lib.star_set_kernel.restype = ctypes.c_int
     lib.star_set_kernel.argtypes = [i32]
     lib.star_plan_claims.restype = ctypes.c_int
-    lib.star_plan_claims.argtypes = [i32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.star_plan_claims.argtypes = [i32, i32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.star_set_queue_threshold.restype = ctypes.c_int
     lib.star_set_queue_threshold.argtypes = [ctypes.c_int64]
     lib.star_workspace_bytes.restype = ctypes.c_size_t
@@ -329,12 +329,13 @@ def star_set_kernel(kernel: int) -> None:
     _check(load_library().star_set_kernel(kernel))
 
 
-def star_plan_claims(workgroups: int):
+def star_plan_claims(workgroups: int, tiles_per_claim: int = 3):
     """(first_tile[G], count[G], base) of the work queue's fixed first round."""
     first = np.zeros(max(workgroups, 1), np.int64)
     count = np.zeros(max(workgroups, 1), np.int32)
     base = ctypes.c_int64(0)
-    _check(load_library().star_plan_claims(workgroups, first.ctypes.data, count.ctypes.data, ctypes.byref(base)))
+    _check(load_library().star_plan_claims(workgroups, tiles_per_claim, first.ctypes.data, count.ctypes.data,
+                                           ctypes.byref(base)))
     return first, count, int(base.value)
 
 

@@ -606,12 +606,14 @@ star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hpar
     return STAR_OK;
 }
 
-star_status star_plan_claims(int32_t workgroups, int64_t* first_tile, int32_t* count, int64_t* base) {
+star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_t* first_tile, int32_t* count,
+                             int64_t* base) {
     g_err.clear();
     if (workgroups < 1) return set_err(STAR_ERR_SHAPE, "workgroups must be positive");
+    if (tiles_per_claim < 1) return set_err(STAR_ERR_SHAPE, "tiles_per_claim must be positive");
     if (!first_tile || !count || !base) return set_err(STAR_ERR_NULL, "an output pointer is NULL");
     for (int32_t b = 0; b < workgroups; ++b) {
-        const star::FirstClaim f = star::first_claim_of(b, workgroups, star::kClaim);
+        const star::FirstClaim f = star::first_claim_of(b, workgroups, tiles_per_claim);
         first_tile[b] = f.t0;
         count[b] = f.n;
         *base = (int64_t)f.base;

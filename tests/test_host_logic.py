@@ -72,12 +72,13 @@ def test_set_kernel_validation():
     assert lib.star_set_queue_threshold(0) == 0
 
 
+@pytest.mark.parametrize("claim", [1, 3, 5])
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 255, 256, 257, 512, 608, 1024])
-def test_first_round_of_claims_tiles_the_front_of_the_shard(G):
+def test_first_round_of_claims_tiles_the_front_of_the_shard(G, claim):
     """The fixed first claims are disjoint, leave no gap, start at tile 0 and end where the counter
-    takes over; their sizes cycle 1, 2, 3 (unequal, so that workgroups do not run in step)."""
-    first, count, base = star.star_plan_claims(G)
-    assert count.tolist() == [1 + b % 3 for b in range(G)]
+    takes over; their sizes cycle 1, 2, .., claim (unequal, so that workgroups do not run in step)."""
+    first, count, base = star.star_plan_claims(G, claim)
+    assert count.tolist() == [1 + b % claim for b in range(G)]
     covered = np.zeros(base, np.int32)
     for b in range(G):
         covered[first[b]:first[b] + count[b]] += 1
@@ -86,8 +87,9 @@ def test_first_round_of_claims_tiles_the_front_of_the_shard(G):
 
 def test_plan_claims_validation():
     lib = star.load_library()
-    assert lib.star_plan_claims(0, None, None, None) == 2
-    assert lib.star_plan_claims(4, None, None, None) == 1
+    assert lib.star_plan_claims(0, 3, None, None, None) == 2
+    assert lib.star_plan_claims(4, 0, None, None, None) == 2
+    assert lib.star_plan_claims(4, 3, None, None, None) == 1
 
 
 def _rand_stream(rng, W, U, stale=None):
