@@ -98,7 +98,8 @@ typedef enum {
     STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
                                matrix behind the norms in vector registers up to 16 rows             */
     STAR_KERNEL_AFFINE_MFMA = 3 /* the same map, the Gram matrix formed on the matrix cores for any number
-                                   of rows (what AUTO uses when it picks the collapsed evaluation)    */
+                                   of rows (what AUTO uses with the collapsed evaluation, except for
+                                   up to 6 fp32 rows, where it keeps the vector registers)            */
 } star_kernel;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is

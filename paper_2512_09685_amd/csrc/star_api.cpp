@@ -199,6 +199,19 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
     return std::max(ng, useq) * (size_t)grid_cap + ng;
 }
 
+// Where the Gram matrix behind the norms is formed.  On the matrix cores, except for a few fp32 rows: the
+// fp32 matrix instructions cost the same for 1 row as for 16 (64 per wave and tile, about 0.85 us), which a
+// tile of few rows does not hide, while the vector-register form needs only W(W+1)/2 accumulators there
+// (110 M elements, norms on: 1 row 0.37 against 0.49 ms, 4 rows 0.53 against 0.64, 6 rows 0.70 against 0.73;
+// from 8 rows on the matrix cores are ahead, and for bf16 rows, whose instructions are 16 times cheaper,
+// at every row count).
+bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice) {
+    if (Wp > star::kMaxValuGramW) return true;
+    if (choice == STAR_KERNEL_AFFINE) return false;
+    if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
+    return !(grad_dtype == STAR_F32 && Wp <= 6);
+}
+
 // The shared body of star_group_update (update = true) and star_group_norms.
 star_status run(bool update, float* params, float* momentum, const void* const* grad_rows, int grad_dtype,
                 int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode,
@@ -327,8 +340,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish_dtype = publish_dtype;
             a.partials = partials;
             a.queue = want_queue ? queue : nullptr;
-            // Gram matrix on the matrix cores; in vector registers only when that kernel is asked for (<= 16 rows)
-            const bool mfma = gram && (Wp > star::kMaxValuGramW || g_kernel_choice.load() != STAR_KERNEL_AFFINE);
+            const bool mfma = gram && gram_on_matrix_cores(Wp, grad_dtype, g_kernel_choice.load());
             if (mfma) a.queue = queue;   // that kernel always takes its tiles from the queue
             e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
                      : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
@@ -538,7 +550,7 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     a.queue = slot->queue;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
-    const bool mfma = Wp > star::kMaxValuGramW || g_kernel_choice.load() != STAR_KERNEL_AFFINE;
+    const bool mfma = gram_on_matrix_cores(Wp, (int)grad_dtype, g_kernel_choice.load());
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, (int)grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");
