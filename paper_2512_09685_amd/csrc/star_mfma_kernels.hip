@@ -29,7 +29,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 // Matrix tiles.  "Row" is a gradient row (a worker), "slot" a group of lanes that feeds one part of
 // the reduction dimension; lane l feeds row l % N and slot l / N.
 //   fp32 rows, N=16: v_mfma_f32_16x16x4_f32,   1 element per lane, 4 slots
-//   fp32 rows, N=32: v_mfma_f32_32x32x2_f32,   1 element per lane, 2 slots
+//   fp32 rows, N=32: three 16x16 blocks by v_mfma_f32_16x16x4_f32 with A and B from the two halves of
+//                    the rows (see kBlocks in the kernel); the 32x32x2 instruction is not used
 //   bf16 rows, N=16: v_mfma_f32_16x16x32_bf16, 8 elements per lane, 4 slots
 //   bf16 rows, N=32: v_mfma_f32_32x32x16_bf16, 8 elements per lane, 2 slots
 // (products of two bf16 values are exact in fp32, so the bf16 instructions lose nothing; they
@@ -57,7 +58,7 @@ template <>
 struct GramTile<true> {
     static constexpr int N = 32, SLOTS = 2, REGS = 16;
     typedef f32x16 acc_t;
-    static __device__ __forceinline__ acc_t mma(float x, acc_t c) {
+    static __device__ __forceinline__ acc_t mma(float x, acc_t c) {   // not reached: fp32 rows go by blocks
         return __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, c, 0, 0, 0);
     }
     static __device__ __forceinline__ acc_t mma(bf16x8 x, acc_t c) {
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
     constexpr int NG = W * (W + 1) / 2;
     constexpr int kWaves = kBlock / 64;
     constexpr int kPanelBytes = N * kPanelRowBytes;
-    static_assert(kPanelBytes >= 64 * GT::REGS * 8, "the panel doubles as the reduction buffer");
+    static_assert(kPanelBytes >= 64 * 16 * 8, "the panel doubles as the reduction buffer");
     __shared__ __align__(16) unsigned char panel[kWaves][kPanelBytes];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -107,6 +108,23 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
         acc2[r] = 0.0;
     }
     const unsigned char* const my_row = T + (lane % N) * kPanelRowBytes + 16 * (lane / N);
+    // 17-32 fp32 rows: the 32x32 matrix is formed from its three distinct 16x16 blocks (rows 0-15 with
+    // themselves, rows 0-15 with rows 16-31, rows 16-31 with themselves) by the 16x16x4 instruction with
+    // A and B from the two halves -- three quarters of the matrix work of the 32x32x2 instruction, which
+    // computes the mirrored block too and is what bounds this variant.  blk[0..2] / blkb[0..2] are the
+    // alternating accumulator sets of the three blocks, blk2 their sums in double.
+    constexpr bool kBlocks = WIDE && !BF;
+    f32x4 blk[3], blkb[3];
+    double blk2[12];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        blk[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        blkb[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+#pragma unroll
+    for (int r = 0; r < 12; ++r) blk2[r] = 0.0;
+    const unsigned char* const my_lo = T + (lane % 16) * kPanelRowBytes + 16 * (lane / 16);
+    const unsigned char* const my_hi = my_lo + 16 * kPanelRowBytes;
 
     // stage: 512 bytes per row (8 per lane) into the panel; consume: feed them to the matrix cores.
     auto stage = [&](const u32x2 (&x)[W]) {
@@ -115,6 +133,22 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
     };
     auto consume = [&]() {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the panel is written before any lane reads it
+        if constexpr (kBlocks) {
+#pragma unroll
+            for (int m = 0; m < 512 / 64; ++m) {   // 4 slots of 16 bytes per row and step
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(my_lo + 64 * m);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(my_hi + 64 * m);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4(&dst)[3] = (j & 1) ? blkb : blk;
+                    dst[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(lo[j], lo[j], dst[0], 0, 0, 0);
+                    dst[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(lo[j], hi[j], dst[1], 0, 0, 0);
+                    dst[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(hi[j], hi[j], dst[2], 0, 0, 0);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            return;
+        }
         constexpr int kReads = 512 / (16 * GT::SLOTS);
 #pragma unroll
         for (int m = 0; m < kReads; ++m) {
@@ -159,6 +193,17 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
     // far below the fp32 the norms are returned in, so that they come out the same every run.
     // The fold is 4 or 16 additions per lane.
     auto fold = [&]() {
+        if constexpr (kBlocks) {
+#pragma unroll
+            for (int b = 0; b < 3; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    blk2[4 * b + r] += (double)(blk[b][r] + blkb[b][r]);
+                    blk[b][r] = 0.0f;
+                    blkb[b][r] = 0.0f;
+                }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < GT::REGS; ++r) {
             acc2[r] += (double)(acc[r] + accb[r]);
@@ -276,8 +321,15 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
     // workgroup total of every Gamma entry, in double, one partial per workgroup; each wave's
     // accumulators go through its own (now idle) panel
     double* const red = reinterpret_cast<double*>(T);
+    if constexpr (kBlocks) {
 #pragma unroll
-    for (int r = 0; r < GT::REGS; ++r) red[lane * GT::REGS + r] = (double)(acc[r] + accb[r]) + acc2[r];
+        for (int b = 0; b < 3; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[lane * 12 + 4 * b + r] = (double)(blk[b][r] + blkb[b][r]) + blk2[4 * b + r];
+    } else {
+#pragma unroll
+        for (int r = 0; r < GT::REGS; ++r) red[lane * GT::REGS + r] = (double)(acc[r] + accb[r]) + acc2[r];
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < NG; e += kBlock) {
         int i = 0, rem = e;
@@ -286,7 +338,16 @@ __global__ __launch_bounds__(kBlock, 2) void aff_mfma_kernel(float* __restrict__
             ++i;
         }
         const int j = i + rem;
-        const int src = GT::lane_of(i, j) * GT::REGS + GT::reg_of(i);
+        int src;
+        if constexpr (kBlocks) {
+            // entry (i, j), i <= j, lies in block 0 (both below 16), 1 (i below, j from 16 on) or 2; inside a
+            // block, D[a][b] is register a % 4 of lane 16 * (a / 4) + b
+            const int b = (i >= 16) ? 2 : (j >= 16 ? 1 : 0);
+            const int a = i & 15, c = j & 15;
+            src = (16 * (a / 4) + c) * 12 + 4 * b + (a % 4);
+        } else {
+            src = GT::lane_of(i, j) * GT::REGS + GT::reg_of(i);
+        }
         double s = 0.0;
 #pragma unroll
         for (int q = 0; q < kWaves; ++q) s += reinterpret_cast<const double*>(panel[q])[src];
