@@ -361,12 +361,13 @@ template <int W, class R, bool UPDATE, bool WIDE>
 hipError_t launch_mfma_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
     auto kern = aff_mfma_kernel<W, R, UPDATE, WIDE>;
     // Long-lived workgroups, tiles from the queue.  Two per compute unit, so that one wave's Gram phase overlaps
-    // another's loads; one where a single workgroup already keeps 64 KB and more in flight, looks a tile
-    // ahead and writes the state (16 fp32 rows: 1.51 against 1.56 ms on the 110 M shard; the norms alone,
-    // a pure read, run 1.13 against 1.24 ms with two).  The LDS panels (33 KB narrow, 66 KB
+    // another's loads; one where a single workgroup already keeps about 48 KB and more in flight, looks a
+    // tile ahead and writes the state (10 to 16 fp32 rows: 2-5 % faster with one, e.g. 16 rows 1.51 against
+    // 1.56 ms on the 110 M shard; 8 rows no difference; the norms alone, a pure read, run 1.13 against
+    // 1.24 ms with two).  The LDS panels (33 KB narrow, 66 KB
     // wide per workgroup) allow both.
     constexpr int kRowBytes = W * (int)sizeof(typename R::vec);
-    const int per_cu = (UPDATE && !WIDE && kRowBytes >= 256) ? 1 : 2;
+    const int per_cu = (UPDATE && !WIDE && kRowBytes >= 160) ? 1 : 2;
     if (!a.queue) return hipErrorInvalidValue;
     const Geometry g = queue_geometry(num_cu, grid_cap, per_cu, kRowBytes + (UPDATE ? 32 : 0));
     *grid_out = g.grid;
