@@ -252,3 +252,30 @@ def test_bench_kernel_digest_ignores_comments_only():
         assert bench.kernel_source_digest() != base
     finally:
         builtins.open = real_open
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/star.h compiles as C (gcc -std=c99 -pedantic), a C program that takes the address of every
+    declared entry point links against libstar.so, and its host-only calls run without a GPU."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "star.h")).read()
+    names = sorted(set(re.findall(r"^(?:star_status|size_t|void|const char \*)\s*(star_[a-z_0-9]+)\s*\(", header, re.M)))
+    assert "star_group_update" in names and "star_group_norms" in names and "star_version" in names
+    src = tmp_path / "abi.c"
+    body = "\n".join(f"    sink((void (*)(void))&{n});" for n in names)
+    src.write_text(
+        '#include "star.h"\n#include <stdio.h>\nstatic int count;\n'
+        "static void sink(void (*f)(void)) { if (f) ++count; }\n"
+        "int main(void) {\n" + body + "\n"
+        "    if (star_set_kernel(99) != STAR_ERR_KERNEL) return 2;\n"
+        "    if (star_set_kernel(STAR_KERNEL_AUTO) != STAR_OK) return 3;\n"
+        '    printf("%d %s\\n", count, star_version());\n    return 0;\n}\n')
+    exe = tmp_path / "abi"
+    lib_dir = os.path.dirname(star.library_path())
+    star.load_library()          # builds the library if there is none
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src),
+                        "-o", str(exe), "-L", lib_dir, "-lstar", "-Wl,-rpath," + lib_dir], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.split()[0] == str(len(names)), (r.returncode, r.stdout, r.stderr)
