@@ -90,8 +90,8 @@ def kernel_label(star, wl, us):
     if wl.grad_dtype == "bf16" and FORCED_KERNEL != "seq":
         k = star.KERNEL_AFFINE      # star_plan_choice answers for fp32 rows; bf16 rows never take the literal kernel
     if k == star.KERNEL_AFFINE:
-        few_f32 = wl.grad_dtype == "f32" and wl.W <= 6      # the library keeps the vector-register Gram there
-        if wl.norms and (wl.W > 16 or FORCED_KERNEL == "affine_mfma" or (FORCED_KERNEL != "affine" and not few_f32)):
+        few = wl.W <= 6                                     # the library keeps the vector-register Gram there
+        if wl.norms and (wl.W > 16 or FORCED_KERNEL == "affine_mfma" or (FORCED_KERNEL != "affine" and not few)):
             return f"aff_mfma_kernel<{wl.W}, {dt}, update, {'wide' if wl.W > 16 else 'narrow'}>", fs, fa
         return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
     return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa

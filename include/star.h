@@ -99,7 +99,7 @@ typedef enum {
                                matrix behind the norms in vector registers up to 16 rows             */
     STAR_KERNEL_AFFINE_MFMA = 3 /* the same map, the Gram matrix formed on the matrix cores for any number
                                    of rows (what AUTO uses with the collapsed evaluation, except for
-                                   up to 6 fp32 rows, where it keeps the vector registers)            */
+                                   up to 6 rows, where it keeps the vector registers)                 */
 } star_kernel;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is

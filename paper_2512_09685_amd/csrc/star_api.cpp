@@ -199,17 +199,18 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
     return std::max(ng, useq) * (size_t)grid_cap + ng;
 }
 
-// Where the Gram matrix behind the norms is formed.  On the matrix cores, except for a few fp32 rows: the
-// fp32 matrix instructions cost the same for 1 row as for 16 (64 per wave and tile, about 0.85 us), which a
-// tile of few rows does not hide, while the vector-register form needs only W(W+1)/2 accumulators there
-// (110 M elements, norms on: 1 row 0.37 against 0.49 ms, 4 rows 0.53 against 0.64, 6 rows 0.70 against 0.73;
-// from 8 rows on the matrix cores are ahead, and for bf16 rows, whose instructions are 16 times cheaper,
-// at every row count).
+// Where the Gram matrix behind the norms is formed.  On the matrix cores, except for up to 6 rows: the
+// matrix instructions cost the same for 1 row as for 16 (fp32: 64 per wave and tile, about 0.85 us),
+// which a tile of few rows does not hide, while the vector-register form needs only W(W+1)/2 <= 21
+// accumulators there and takes its tiles from the queue as well (norms on, 8 updates: 1 fp32 row 0.34
+// against 0.49 ms on 100 M elements, 4 rows 0.53 against 0.64; 1 bf16 row 0.59 against 0.66 ms on 200 M
+// elements; 6 rows equal, 7 and 8 rows 2-6 % behind).
 bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
     if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
-    return !(grad_dtype == STAR_F32 && Wp <= 6);
+    (void)grad_dtype;
+    return Wp > star::kFewRows;
 }
 
 // The shared body of star_group_update (update = true) and star_group_norms.
@@ -547,10 +548,10 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     a.P = P;
     a.vec_ok = vec_ok ? 1 : 0;
     a.partials = slot->partials;
-    a.queue = slot->queue;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
     const bool mfma = gram_on_matrix_cores(Wp, (int)grad_dtype, g_kernel_choice.load());
+    a.queue = (mfma || P >= g_queue_min.load()) ? slot->queue : nullptr;
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, (int)grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");

@@ -10,6 +10,7 @@
 namespace star {
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wave64
+constexpr int kFewRows = 6;          // up to this many rows the Gram matrix behind the norms stays in vector registers
 constexpr int kGridCap = 1024;       // most workgroups a norm-reducing launch uses (sizes the partial buffer)
 
 // Work queue of one launch: the next tile nobody has claimed yet and the number of workgroups that

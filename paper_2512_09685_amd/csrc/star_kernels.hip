@@ -57,13 +57,27 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
     // of products is longer than 4*kGramFold terms: long chains of squares of
     // short-mantissa (bf16) values round down systematically, about 1e-9 per
     // term, because the low bits of a square are not uniformly distributed.
-    __shared__ float fold[GRAM ? NG * kBlock : 1];
+    // With few rows (up to kFewRows) there are few pairs: the slots are double and take the sums after
+    // every chunk, which makes them independent of the order of the tiles (to 1e-16), so that this
+    // variant can take its tiles from the queue like the plain one; and it has the registers for it.
+    constexpr bool kFew = GRAM && W <= kFewRows;
+    typedef typename std::conditional<kFew, double, float>::type fold_t;
+    __shared__ fold_t fold[GRAM ? NG * kBlock : 1];
     if constexpr (GRAM) {
 #pragma unroll
-        for (int e = 0; e < NG; ++e) fold[e * kBlock + threadIdx.x] = 0.0f;
+        for (int e = 0; e < NG; ++e) fold[e * kBlock + threadIdx.x] = (fold_t)0;
     }
+    auto fold_now = [&]() {
+        if constexpr (GRAM) {
+#pragma unroll
+            for (int e = 0; e < NG; ++e) {
+                fold[e * kBlock + threadIdx.x] += (fold_t)acc[e];
+                acc[e] = 0.0f;
+            }
+        }
+    };
 
-    // the Gram variant is always launched with kBlock threads (its LDS slots are laid out for that);
+    // the Gram variants are always launched with kBlock threads (their LDS slots are laid out for that);
     // the plain one also runs with half-size workgroups
     const int threads = GRAM ? kBlock : (int)blockDim.x;
     const Span span = make_span(span_g, span_k, threads);
@@ -109,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
         }
     };
     bool queued = false;
-    if constexpr (!GRAM) {
+    if constexpr (!GRAM || kFew) {
         // without the register-heavy Gram accumulators the kernel affords a second copy of the chunk
         // code: tiles from the queue for long shards, a fixed assignment for short ones
         if (claim > 0) {
@@ -117,23 +131,21 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
             const int64_t ntile = (nchunk + threads - 1) / threads;
             for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
                 const int64_t c = tile * threads + threadIdx.x;
-                if (c < nchunk) process(c);
+                if (c < nchunk) {
+                    process(c);
+                    if constexpr (kFew) fold_now();
+                }
             });
         }
     }
     if (!queued) {
         int64_t c = span.first;
         for (int k = 0; k < span.K && c < nchunk; ++k, c += span.step) {
-            if constexpr (GRAM) {
-                if ((k & (kGramFold - 1)) == kGramFold - 1) {
-#pragma unroll
-                    for (int e = 0; e < NG; ++e) {
-                        fold[e * kBlock + threadIdx.x] += acc[e];
-                        acc[e] = 0.0f;
-                    }
-                }
+            if constexpr (GRAM && !kFew) {
+                if ((k & (kGramFold - 1)) == kGramFold - 1) fold_now();
             }
             process(c);
+            if constexpr (kFew) fold_now();
         }
     }
     // elements not covered by whole chunks (the ragged end, or everything when
@@ -156,11 +168,11 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
     }
 
     if constexpr (GRAM) {
-        __shared__ float wave_part[kBlock / 64][NG];
+        __shared__ fold_t wave_part[kBlock / 64][NG];
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
         for (int e = 0; e < NG; ++e) {
-            const float s = wave_sum_to_lane63(acc[e] + fold[e * kBlock + threadIdx.x]);
+            const fold_t s = wave_sum_to_lane63((fold_t)acc[e] + fold[e * kBlock + threadIdx.x]);
             if (lane == 63) wave_part[wave][e] = s;
         }
         __syncthreads();
@@ -433,7 +445,7 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
     // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = !GRAM && a.queue && a.vec_ok;
+    const bool queued = (!GRAM || W <= kFewRows) && a.queue && a.vec_ok;
     Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes)
                         : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     // 24 and more bf16 rows: twice as many workgroups of half the size (tiles of 1 KB per row) measured
