@@ -209,6 +209,27 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     return res
 
 
+def device_copy_gbps(torch):
+    """Bandwidth of a plain device-to-device copy of 1 GiB (read + written bytes over time), for context: what
+    the memory system gives the simplest mixed read / write stream."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < WAKEUP_SECONDS:
+        dst.copy_(src)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    gbps = 10 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+    return gbps
+
+
 def cpu_baseline(wl, torch, workloads):
     """The CPU oracle (exact fp64 mode, one thread) on a contiguous slice of the
     same workload, sized for roughly 15 s; elements are independent, so the
@@ -276,6 +297,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    copy_gbps = device_copy_gbps(torch)
     head = measure(head_wl, a.steps, a.warmup, torch, star, workloads, a.op)
     per_config = []
     if not a.only:
@@ -305,6 +327,8 @@ def main():
                         else None),
             "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
+            "device_copy_gbps": copy_gbps,
+            "frac_of_device_copy": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / copy_gbps,
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "
                     "norm-finishing kernels that follow each update kernel",
         },
