@@ -261,8 +261,10 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
         if (k < Wc && !aligned16(rows.p[k])) vec_ok = false;
     }
 
-    // tables of the step-by-step kernel: in the kernel arguments when small, else staged through the slot
-    const bool seq_inline = route != star::Route::Affine && star::tables_fit_inline(U, Wp);
+    // tables of the step-by-step kernel: in the kernel arguments when small and the whole stream fits in
+    // one launch (a launch reads the inline tables from entry 0), else staged through the slot
+    const bool seq_inline = route != star::Route::Affine && star::tables_fit_inline(U, Wp) &&
+                            U <= star::seq_max_updates(Wp, want_norms);
     star::InlineTables inl;
     if (seq_inline) {
         for (int u = 0; u < U; ++u) {
@@ -440,7 +442,8 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
     SlotRelease release{slot, stream};
     char* h = static_cast<char*>(slot->host);
     char* d = static_cast<char*>(slot->dev);
-    const bool use_inline = star::tables_fit_inline(U, Wp);
+    // inline tables only when one launch takes the whole stream: a launch reads them from entry 0
+    const bool use_inline = star::tables_fit_inline(U, Wp) && U <= star::reduce_max_updates(Wp, want_norms);
     star::InlineTables inl;
     if (use_inline) {
         for (int u = 0; u < U; ++u) {

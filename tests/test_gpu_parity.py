@@ -37,6 +37,8 @@ def check(p, v, n, ep, ev, en, dtype, what=""):
     # short streams (the step-by-step kernel is queue-ordered up to 4 updates) and shards of more tiles than
     # the first, fixed round of claims covers (256 or 512 workgroups x 2 tiles on average)
     (8, 300007, 2, True), (16, 1300003, 3, True), (16, 1300003, 16, True), (6, 1100000, 1, False),
+    # streams that the step-by-step kernel splits over two launches although their tables are small
+    (8, 4099, 32, True), (8, 4099, 30, True), (1, 4099, 32, True),
 ])
 def test_random_shapes(dtype, kname, W, P, U, norms):
     rng = np.random.default_rng(1000 * W + U + (7 if dtype == "bf16" else 0))

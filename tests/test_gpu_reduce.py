@@ -31,6 +31,8 @@ def run_reduce(rows_np, offs, mem, st, out_dtype, norms, P, wmode="stale", shift
 @pytest.mark.parametrize("W,P,U,norms", [
     (1, 1, 1, True), (2, 3, 2, False), (5, 1025, 1, True), (4, 4099, 3, False), (16, 70001, 5, True),
     (17, 33333, 2, True), (32, 50001, 4, False), (8, 300007, 1, True), (6, 20011, 70, True), (3, 9001, 200, False),
+    # streams that need two launches although their tables are small enough for the kernel arguments
+    (1, 5003, 32, True), (6, 5003, 30, True), (8, 5003, 29, True), (8, 5003, 32, True),
 ])
 def test_reduce_random_shapes(in_dtype, out_dtype, W, P, U, norms):
     rng = np.random.default_rng(31 * W + U)
