@@ -134,6 +134,31 @@ star_status star_group_update(float *params, float *momentum, const void *const 
                               const star_hparams *hp, float *norms_out, void *hip_stream);
 
 /*
+ * star_group_update for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels, same results.  Where star_group_update keeps
+ * its tables, per-workgroup partial sums and tile queue in a workspace it
+ * allocates on first use, this entry point keeps them in a fixed array of
+ * STAR_NOALLOC_SCRATCH_BYTES that is part of the library's device code (every
+ * GPU the library runs on holds one copy until the process ends), and carries
+ * the group tables to it in kernel arguments.  It calls no hipMalloc, hipFree,
+ * hipHostMalloc, event or copy routine.
+ *   - at most STAR_NOALLOC_MAX_UPDATES updates per call; a longer stream is
+ *     rejected with STAR_ERR_SHAPE before anything is enqueued (split it over
+ *     several calls, the state carries over).
+ *   - all calls on one GPU share that GPU's array: two calls of this entry
+ *     point whose work overlaps in time on one GPU (different streams, or
+ *     different host threads) race on it.  Calls on one stream are ordered and
+ *     safe; so are calls on different GPUs.  It never conflicts with the other
+ *     entry points, which do not touch the array.
+ */
+#define STAR_NOALLOC_MAX_UPDATES 256
+#define STAR_NOALLOC_SCRATCH_BYTES (4608 * 1024)
+star_status star_group_update_noalloc(float *params, float *momentum, const void *const *grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
+                                      const star_hparams *hp, float *norms_out, void *hip_stream);
+
+/*
  * star_group_update that also writes a copy of the updated parameters for the
  * "send the updated parameters to the workers" leg (Section 2): after the U
  * updates, publish[j] = params[j] converted to publish_dtype (fp32: the same

@@ -58,6 +58,8 @@ def load_library():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.star_group_update.restype = ctypes.c_int
     lib.star_group_update.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp]
+    lib.star_group_update_noalloc.restype = ctypes.c_int
+    lib.star_group_update_noalloc.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp]
     lib.star_group_update_publish.restype = ctypes.c_int
     lib.star_group_update_publish.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.star_group_norms.restype = ctypes.c_int
@@ -167,6 +169,24 @@ def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStre
     _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
                                  ctypes.byref(updates.c), ctypes.byref(hp),
                                  None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
+
+
+def star_group_update_noalloc(params, momentum, grad_rows: Sequence, updates: UpdateStream, *, lr: float,
+                              momentum_coef: float, weight_decay: float = 0.0, wmode="mean",
+                              scale_lr_by_group: bool = False, norms_out=None, stream=None) -> None:
+    """star_group_update through the entry point that allocates no device memory
+    (its workspace is a fixed array inside the library); at most 256 updates."""
+    lib = load_library()
+    P = int(params.shape[0])
+    if not (params.is_contiguous() and momentum.is_contiguous()) or momentum.shape[0] != P:
+        raise ValueError("params and momentum must be contiguous and of equal length")
+    ptrs, dt = _rows(grad_rows, P)
+    hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
+    if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
+        raise ValueError("norms_out must hold U floats")
+    _check(lib.star_group_update_noalloc(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                         ctypes.byref(updates.c), ctypes.byref(hp),
+                                         None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
 
 
 def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: UpdateStream, publish, *, lr: float,

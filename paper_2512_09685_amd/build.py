@@ -25,7 +25,7 @@ CXX_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-D__HIP_PLATFORM
              "-ffp-contract=off"]
 INCLUDES = ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-I" + os.path.join(ROCM, "include")]
 
-HIP_SOURCES = ["star_kernels.hip", "star_reduce_kernels.hip", "star_mfma_kernels.hip"]
+HIP_SOURCES = ["star_kernels.hip", "star_reduce_kernels.hip", "star_mfma_kernels.hip", "star_scratch.hip"]
 CXX_SOURCES = ["star_api.cpp", "star_plan.cpp", "star_select.cpp"]
 
 

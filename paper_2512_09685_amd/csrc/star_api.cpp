@@ -213,12 +213,18 @@ bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice) {
     return Wp > star::kFewRows;
 }
 
-// The shared body of star_group_update (update = true) and star_group_norms.
+// The shared body of star_group_update (update = true) and star_group_norms.  With `no_alloc` the
+// call works in the fixed device array of star_scratch.hip instead of a workspace slot and allocates
+// no device memory, pinned memory or event.
 star_status run(bool update, float* params, float* momentum, const void* const* grad_rows, int grad_dtype,
                 int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode,
-                float* norms_out, void* publish, int publish_dtype, void* hip_stream) {
+                float* norms_out, void* publish, int publish_dtype, void* hip_stream, bool no_alloc = false) {
     g_err.clear();
     if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
+    if (no_alloc && upd->U > star::kScratchMaxUpdates)
+        return set_err(STAR_ERR_SHAPE, "U=" + std::to_string(upd->U) + " is more than the " +
+                                           std::to_string(star::kScratchMaxUpdates) +
+                                           " updates a call of star_group_update_noalloc accepts");
     if (update && !hp) return set_err(STAR_ERR_NULL, "hyper-parameter struct is NULL");
     if (!update && !norms_out) return set_err(STAR_ERR_NULL, "norms_out is NULL");
     if (!grad_rows) return set_err(STAR_ERR_NULL, "grad_rows is NULL");
@@ -282,17 +288,36 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const bool need_slot = need_seq_tables || need_gram_coef || want_norms || want_queue;
     std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
     Slot* slot = nullptr;
-    if (need_slot) {
+    std::vector<char> host_tables;   // no_alloc: the tables are built here and travel in kernel arguments
+    char *h = nullptr, *d = nullptr;
+    double* partials = nullptr;
+    star::TileQueue* queue = nullptr;
+    if (need_slot && no_alloc) {
+        const size_t need_partials = want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0;
+        if (lay.total > star::kScratchTableBytes || need_partials > star::kScratchPartialDoubles)
+            return set_err(STAR_ERR_SHAPE, "the call needs more workspace than the fixed array of "
+                                           "star_group_update_noalloc holds");
+        void* base = nullptr;
+        STAR_HIP(star::scratch_address(&base));
+        queue = static_cast<star::TileQueue*>(base);
+        d = static_cast<char*>(base) + 256;
+        partials = reinterpret_cast<double*>(d + star::kScratchTableBytes);
+        host_tables.assign(lay.total, 0);
+        h = host_tables.data();
+        // the array keeps what the last call left: the queue must start at zero (a call that failed
+        // half-way may not have put it back); tables and partials are written before they are read
+        STAR_HIP(star::launch_queue_clear(queue, stream));
+    } else if (need_slot) {
         lock.lock();
         st = acquire_slot(device, (need_seq_tables || need_gram_coef) ? lay.total : 0,
                           want_norms ? partial_doubles_needed(Wp, U, grid_cap) : 0, &slot);
         if (st != STAR_OK) return st;
+        h = static_cast<char*>(slot->host);
+        d = static_cast<char*>(slot->dev);
+        partials = slot->partials;
+        queue = slot->queue;
     }
     SlotRelease release{slot, stream};
-    char* h = slot ? static_cast<char*>(slot->host) : nullptr;
-    char* d = slot ? static_cast<char*>(slot->dev) : nullptr;
-    double* partials = slot ? slot->partials : nullptr;
-    star::TileQueue* queue = slot ? slot->queue : nullptr;
     if (need_seq_tables) {
         float* c32 = reinterpret_cast<float*>(h + lay.coef32);
         float* l32 = reinterpret_cast<float*>(h + lay.lr32);
@@ -311,10 +336,18 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     // The step-by-step tables are read by every workgroup and are copied to the device.  The Gram
     // coefficients (a few KB, read once, by the one small kernel that ends the call) are read where they
     // are, in the slot's pinned host buffer: no copy engine in the stream.
-    if (need_seq_tables) STAR_HIP(hipMemcpyAsync(d, h, lay.coef64, hipMemcpyHostToDevice, stream));
-    const double* gram_coef = (slot && slot->host_dev)
-                                  ? reinterpret_cast<const double*>(static_cast<char*>(slot->host_dev) + lay.coef64)
-                                  : nullptr;
+    const double* gram_coef = nullptr;
+    if (no_alloc) {
+        if (need_seq_tables) STAR_HIP(star::launch_upload(d, h, lay.coef64, stream));
+        if (need_gram_coef) {
+            STAR_HIP(star::launch_upload(d + lay.coef64, h + lay.coef64, sizeof(double) * (size_t)U * Wp, stream));
+            gram_coef = reinterpret_cast<const double*>(d + lay.coef64);
+        }
+    } else {
+        if (need_seq_tables) STAR_HIP(hipMemcpyAsync(d, h, lay.coef64, hipMemcpyHostToDevice, stream));
+        if (slot && slot->host_dev)
+            gram_coef = reinterpret_cast<const double*>(static_cast<char*>(slot->host_dev) + lay.coef64);
+    }
 
     hipError_t e = hipSuccess;
     int grid = 0;
@@ -497,6 +530,13 @@ star_status star_group_update(float* params, float* momentum, const void* const*
                               int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
                               float* norms_out, void* hip_stream) {
     return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, hip_stream);
+}
+
+star_status star_group_update_noalloc(float* params, float* momentum, const void* const* grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
+                                      const star_hparams* hp, float* norms_out, void* hip_stream) {
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, hip_stream,
+               true);
 }
 
 star_status star_group_update_publish(float* params, float* momentum, const void* const* grad_rows,

@@ -146,6 +146,28 @@ hipError_t launch_gram_unpack(const double* gamma, int Wp, int W, double* out, h
 
 hipError_t launch_fill(float* dst, int64_t n, float value, hipStream_t s);
 
+// ---- the fixed device workspace of the entry point that allocates nothing
+// One array of kScratchBytes per GPU, part of the library's device code (no hipMalloc behind it):
+//   [0, 256)                                   the tile queue
+//   [256, 256 + kScratchTableBytes)            group tables
+//   [256 + kScratchTableBytes, kScratchBytes)  per-workgroup partial sums and the reduced Gram matrix
+constexpr int kScratchMaxUpdates = 256;                       // longest stream that entry point accepts
+constexpr size_t kScratchTableBytes = 128 * 1024;             // tables of 256 updates over 32 rows: 100 KB
+constexpr size_t kScratchPartialDoubles = 528 * (size_t)kGridCap + 528;   // Gram partials of 32 rows
+constexpr size_t kScratchBytes = 4608 * 1024;                 // 4.5 MiB
+static_assert(256 + kScratchTableBytes + kScratchPartialDoubles * sizeof(double) <= kScratchBytes,
+              "the three parts fit in the array");
+
+// Device address of the array on the current device (resolved once per device, then cached).
+hipError_t scratch_address(void** out);
+
+// dst[0..bytes) = src[0..bytes): host data carried to the device in kernel arguments, a few KB per
+// launch -- no copy engine, no staging buffer, nothing allocated.  dst 16-byte aligned.
+hipError_t launch_upload(void* dst_dev, const void* src_host, size_t bytes, hipStream_t s);
+
+// Puts a tile queue back to "no tile claimed, nobody left".
+hipError_t launch_queue_clear(TileQueue* q, hipStream_t s);
+
 // ---- aggregation without the optimizer step (star_group_reduce)
 struct ReduceArgs {
     RowPtrs rows;
