@@ -19,15 +19,14 @@ import time
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 WAKEUP_SECONDS = 0.08    # untimed work before the warm-up steps, see measure()
+FIRST_CALL_IDLE = 0.25   # seconds the device idles before each "first call" sample
+FIRST_CALL_REPS = 5
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (each scaled by what
-# the same counter reads for a plain 1 GiB copy); valid only for the kernel sources (star_kernels.hip,
-# star_mfma_kernels.hip and star_device.h, hashed together without comments and white space) they were taken with.
-MEASURED_TRAFFIC = {
-    "kernels_sha256": "e78f5f4f835794cd505e39612feb03ba34bacc307279f2cb5b2dfcbdc0feeced",
-    "bytes_per_launch": {"resnet50": 1227068410, "bert_base": 8802182393, "vgg16": 11071352457,
-                         "bert_large": 16325392633},
-}
+# the same counter reads for a plain 1 GiB copy).  profiles/measured_traffic.json holds them together with a digest
+# of the kernel sources they were taken with (star_kernels.hip, star_mfma_kernels.hip and star_device.h, hashed
+# without comments and white space); it is written by `python -m paper_2512_09685_amd.rocprof_summary`.
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "measured_traffic.json")
 
 
 def kernel_source_digest():
@@ -46,12 +45,13 @@ def kernel_source_digest():
 
 def measured_traffic(workload):
     try:
+        table = json.load(open(TRAFFIC_FILE))
         digest = kernel_source_digest()
-    except OSError:
+    except (OSError, ValueError):
         return None
-    if digest != MEASURED_TRAFFIC["kernels_sha256"]:
+    if digest != table.get("kernels_sha256"):
         return None            # the kernels changed since the counters were taken
-    return MEASURED_TRAFFIC["bytes_per_launch"].get(workload)
+    return table.get("bytes_per_launch", {}).get(workload)
 
 
 def parse():
@@ -80,21 +80,19 @@ def parse():
     return ap.parse_args()
 
 
-FORCED_KERNEL = "auto"
+KERNEL_OPTION = None      # star_options.kernel of every call (None: the library chooses)
+KERNEL_NAMES = {1: "seq_kernel", 2: "aff_kernel", 3: "aff_mfma_kernel"}
 
 
-def kernel_label(star, wl, us):
-    k, fs, fa = star.star_plan_choice(wl.W, us, lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay,
-                                      wmode=wl.wmode, want_norms=wl.norms)
-    dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
-    if wl.grad_dtype == "bf16" and FORCED_KERNEL != "seq":
-        k = star.KERNEL_AFFINE      # star_plan_choice answers for fp32 rows; bf16 rows never take the literal kernel
-    if k == star.KERNEL_AFFINE:
-        few = wl.W <= 6                                     # the library keeps the vector-register Gram there
-        if wl.norms and (wl.W > 16 or FORCED_KERNEL == "affine_mfma" or (FORCED_KERNEL != "affine" and not few)):
-            return f"aff_mfma_kernel<{wl.W}, {dt}, update, {'wide' if wl.W > 16 else 'narrow'}>", fs, fa
-        return f"aff_kernel<{wl.W}, {dt}, update, {'gram' if wl.norms else 'no-gram'}>", fs, fa
-    return f"seq_kernel<{wl.W}, {'RowF32' if wl.grad_dtype == 'f32' else 'RowBf16x4'}>", fs, fa
+def kernel_label(star, wl, us, op):
+    """Name of the main kernel of a call, from the library's own account of what it launches."""
+    c = star.star_plan_choice(wl.P, wl.W, wl.grad_dtype, us, lr=wl.lr, momentum_coef=wl.momentum,
+                              weight_decay=wl.weight_decay, wmode=wl.wmode, update=op != "norms",
+                              want_norms=wl.norms or op == "norms", kernel=KERNEL_OPTION)
+    row = "RowF32" if c["grad_dtype"] == 0 else "RowBf16x4"
+    what = "norms only" if op == "norms" else ("update+norms" if wl.norms else "update")
+    order = "queue order" if c["queue_order"] else "fixed assignment"
+    return f"{KERNEL_NAMES[c['kernel']]}<{c['rows_padded']}, {row}> {what}, {order}", c
 
 
 def measure(wl, steps, warmup, torch, star, workloads, op="update"):
@@ -127,15 +125,17 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     def step():
         for c in range(wl.calls):
             if op == "update":
-                star.star_group_update(p, v, sets[c % nsets], streams[c], norms_out=norms[c], stream=stream, **hp)
+                star.star_group_update(p, v, sets[c % nsets], streams[c], norms_out=norms[c], stream=stream,
+                                       kernel=KERNEL_OPTION, **hp)
             elif op == "publish":
                 star.star_group_update_publish(p, v, sets[c % nsets], streams[c], pub, norms_out=norms[c],
-                                               stream=stream, **hp)
+                                               stream=stream, kernel=KERNEL_OPTION, **hp)
             elif op == "norms":
-                star.star_group_norms(sets[c % nsets], streams[c], norms[c], wmode=wl.wmode, stream=stream)
+                star.star_group_norms(sets[c % nsets], streams[c], norms[c], wmode=wl.wmode, stream=stream,
+                                      kernel=KERNEL_OPTION)
             else:
                 star.star_group_reduce(out, sets[c % nsets], full, norms_out=None if norms[c] is None else norms[c][:1],
-                                       stream=stream)
+                                       stream=stream, kernel=KERNEL_OPTION)
 
     # Wake-up: after a pause the device needs 25-50 ms of sustained work before step times settle (the first
     # steps run 10-30 % slower), whatever --warmup says; untimed, like the warm-up steps that follow.
@@ -164,12 +164,29 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     per_step = sorted(a.elapsed_time(b) for a, b in zip([e0] + marks[:-1], marks))
     assert bool(torch.isfinite(p[:: max(1, wl.P // 4096)]).all()), "non-finite parameters after the timed steps"
 
+    # A step after a pause: the paper's server is called once per training iteration, 100-800 ms apart
+    # (Section 5.1, overhead of STAR), not back to back.  One step after FIRST_CALL_IDLE seconds of an idle
+    # device, five times; the median is reported beside the steady-state figure.
+    first = []
+    for _ in range(FIRST_CALL_REPS):
+        torch.cuda.synchronize()
+        time.sleep(FIRST_CALL_IDLE)
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record(stream)
+        step()
+        a1.record(stream)
+        stream.synchronize()
+        first.append(a0.elapsed_time(a1))
+    first.sort()
+    first_call_ms = first[len(first) // 2]
+
     # rows referenced per call (each call reads only the rows its own groups name), averaged over the calls
     used = [set(int(x) for x in us.members) for us in streams]
     n_used = sum(len(u) for u in used) / len(used)
     bytes_per_call = int(sum(wl.algorithmic_bytes_per_call(len(u)) for u in used) / len(used)) + extra_bytes
     n_updates = wl.U
-    label, fs, fa = kernel_label(star, wl, streams[0])
+    label, choice = kernel_label(star, wl, streams[0], op)
+    fs, fa = choice["fma_seq"], choice["fma_affine"]
     if op == "reduce":
         bytes_per_call = wl.P * (wl.W * wl.grad_bytes + wl.grad_bytes)      # W rows read, one output row written
         n_updates = 1
@@ -177,15 +194,6 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         fs, fa = float(wl.W + (1 if wl.norms else 0)), None
     if op == "norms":
         bytes_per_call = int(wl.P * n_used * wl.grad_bytes)                 # the referenced rows, read once
-        dt = "RowF32" if wl.grad_dtype == "f32" else "RowBf16x4"
-        k, fs, fa = star.star_plan_choice(wl.W, streams[0], lr=wl.lr, momentum_coef=wl.momentum,
-                                          weight_decay=wl.weight_decay, wmode=wl.wmode, want_norms=True)
-        if k == star.KERNEL_SEQ:
-            label = f"seq_kernel<{wl.W}, {dt}, norms only>"
-        elif FORCED_KERNEL == "affine" and wl.W <= 16:
-            label = f"aff_kernel<{wl.W}, {dt}, norms only, gram>"
-        else:
-            label = f"aff_mfma_kernel<{wl.W}, {dt}, norms only, {'wide' if wl.W > 16 else 'narrow'}>"
     bytes_per_step = bytes_per_call * wl.calls
     gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     res = {
@@ -194,7 +202,9 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
         "group_updates_per_s": n_updates * wl.calls / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms / steps,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
-        "wakeup_steps": n_wake,
+        "wakeup_steps": n_wake, "first_call_ms": first_call_ms,
+        "first_call_hbm_frac": bytes_per_call * wl.calls / (first_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "timed_launches": steps * wl.calls,
         "algorithmic_bytes_per_step": bytes_per_step, "bytes_per_element": bytes_per_call / wl.P,
         "hbm_gbps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "kernel": label,
         "fma_per_element_seq": fs, "fma_per_element_affine": fa,
@@ -231,13 +241,14 @@ def device_copy_gbps(torch):
 
 
 def cpu_baseline(wl, torch, workloads):
-    """The CPU oracle (exact fp64 mode, one thread) on a contiguous slice of the
-    same workload, sized for roughly 15 s; elements are independent, so the
-    full-shard rate is the slice's rate scaled by the slice fraction."""
+    """The CPU oracle, one thread pinned to one core, on a contiguous slice of the same workload; elements are
+    independent, so the full-shard rate is the slice's rate scaled by the slice fraction.  Two timings of about
+    8 s each: the exact mode (fp64 arithmetic, the parity reference; this is `value`) and the stepwise-fp32 mode
+    (what a literal fp32 parameter server computes: add the gradient copies, then update, Section 2)."""
     import numpy as np
     from oracle import star_oracle as so
 
-    def run(P):
+    def run(P, mode):
         w = wl.scaled(P)
         rows = workloads.rows_to_numpy(workloads.make_grad_rows(w, 0, 0, "cpu"))
         p0 = workloads.make_params(w, 0, "cpu").numpy()
@@ -245,23 +256,41 @@ def cpu_baseline(wl, torch, workloads):
         t = time.perf_counter()
         so.group_update(p0, np.zeros_like(p0), rows, s["offsets"], s["members"], staleness=s["staleness"],
                         lr=w.lr, momentum_coef=w.momentum, weight_decay=w.weight_decay, wmode=w.wmode,
-                        want_norms=w.norms, mode="exact")
+                        want_norms=w.norms, mode=mode)
         return time.perf_counter() - t
 
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
     try:
         os.sched_setaffinity(0, {sorted(os.sched_getaffinity(0))[0]})
     except (AttributeError, OSError):
         pass
-    probe_P = 20000
-    t_probe = max(run(probe_P), 1e-4)
-    P = int(min(wl.P, max(probe_P, probe_P * 15.0 / t_probe)))
-    t = run(P)
-    full_call_s = t * wl.P / P
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    out = {}
+    for mode in ("exact", "f32step"):
+        probe_P = 20000
+        t_probe = max(run(probe_P, mode), 1e-4)
+        P = int(min(wl.P, max(probe_P, probe_P * 8.0 / t_probe)))
+        t = run(P, mode)
+        full_call_s = t * wl.P / P
+        out[mode] = (wl.U / full_call_s, wl.algorithmic_bytes_per_call() / full_call_s / 1e9, P, t)
+    v, g, P, t = out["exact"]
+    v32, g32, P32, t32 = out["f32step"]
     return {
-        "value": wl.U / full_call_s, "unit": "group-updates/s", "cores": 1, "kind": "oracle",
+        "value": v, "unit": "group-updates/s", "cores": 1, "kind": "oracle",
         "sample": f"exact-mode (fp64) oracle, one call of U={wl.U} updates on a contiguous slice of {P} of "
                   f"{wl.P} elements in {t:.2f} s, scaled by {wl.P / P:.1f}x (elements are independent)",
-        "gbps": wl.algorithmic_bytes_per_call() / full_call_s / 1e9,
+        "gbps": g,
+        "f32step_value": v32, "f32step_gbps": g32,
+        "f32step_sample": f"stepwise-fp32 oracle (state rounded to fp32 after every update), slice of {P32} elements "
+                          f"in {t32:.2f} s, scaled by {wl.P / P32:.1f}x",
+        "build": "gcc " + " ".join(so.BUILD_FLAGS), "cpu_model": cpu_model, "host_cpus": nproc,
     }
 
 
@@ -279,10 +308,9 @@ def main():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(1)
     star.load_library()
-    global FORCED_KERNEL
-    FORCED_KERNEL = a.kernel
-    star.star_set_kernel({"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE,
-                          "affine_mfma": star.KERNEL_AFFINE_MFMA}[a.kernel])
+    global KERNEL_OPTION
+    KERNEL_OPTION = {"auto": None, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE,
+                     "affine_mfma": star.KERNEL_AFFINE_MFMA}[a.kernel]
     import dataclasses
     wl_of = {n: (w if a.norms == "workload" else dataclasses.replace(w, norms=a.norms == "on"))
              for n, w in workloads.WORKLOADS.items()}
@@ -313,6 +341,9 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": head["ms_per_step"],
         "ms_per_step_median": head["ms_per_step_median"], "ms_per_step_min": head["ms_per_step_min"],
+        "first_call_ms": head["first_call_ms"],
+        "regime": "value, ms_per_step and roofline are steady state (calls back to back after 80 ms of wake-up work "
+                  "and the warm-up steps); first_call_ms is one step after 250 ms of an idle device, median of 5",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": a.workload, "op": a.op, "P": head_wl.P, "W": head_wl.W, "U": head_wl.U * head_wl.calls,
@@ -327,6 +358,7 @@ def main():
                         else None),
             "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
+            "timed_launches": head["timed_launches"],
             "device_copy_gbps": copy_gbps,
             "frac_of_device_copy": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / copy_gbps,
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "

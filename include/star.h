@@ -42,8 +42,15 @@
  *     library neither frees nor keeps them.  Host arrays and structs are
  *     consumed before the call returns.
  *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
- *     the call does not wait for it.  Outputs are valid after the stream has
- *     been synchronised.
+ *     the call does not wait for that work.  Outputs are valid after the
+ *     stream has been synchronised.  Two things can make the host wait inside
+ *     a call all the same: (1) the internal workspace is a ring of 8 slots,
+ *     one per call that needs tables, partial sums or the tile queue, each
+ *     guarded by an event; the ninth such call blocks (hipEventSynchronize)
+ *     until the work of the call that used its slot eight calls earlier has
+ *     finished; (2) the first call that needs a larger workspace than any
+ *     before it allocates device and pinned memory (hipMalloc, hipHostMalloc),
+ *     which synchronises the device.  star_group_update_noalloc does neither.
  *   - The return value is a star_status.  Nothing is thrown, nothing aborts.
  *     All argument checks precede the first enqueue: on a status other than
  *     STAR_OK and STAR_ERR_DEVICE no device memory has been modified.
@@ -78,7 +85,7 @@ typedef enum {
     STAR_ERR_HPARAM = 4, /* non-finite lr / momentum / weight decay / coefficient, negative
                             staleness, unknown weighting mode                                   */
     STAR_ERR_DTYPE = 5,  /* unknown gradient dtype                                             */
-    STAR_ERR_KERNEL = 6, /* unknown kernel choice in star_set_kernel / STAR_KERNEL             */
+    STAR_ERR_KERNEL = 6, /* unknown kernel choice in star_options                              */
     STAR_ERR_DEVICE = 7  /* a HIP call failed; text via star_last_error()                      */
 } star_status;
 
@@ -101,6 +108,27 @@ typedef enum {
                                    of rows (what AUTO uses with the collapsed evaluation, except for
                                    up to 6 rows, where it keeps the vector registers)                 */
 } star_kernel;
+
+/*
+ * Per-call options of the *_opt entry points (host struct, read before the
+ * call returns).  All zero = the defaults; a NULL pointer means the same.
+ * Nothing here changes what is computed, only how (both evaluations and both
+ * tile orders give the same params and momentum up to fp32 rounding, see
+ * star_plan_affine), so these are tuning and test switches.  There is no
+ * process-wide setting: two callers in one process may use different options
+ * at the same time.  The environment variable STAR_KERNEL=seq|affine|
+ * affine_mfma, read once at load time, replaces STAR_KERNEL_AUTO for calls
+ * that do not choose themselves.
+ */
+typedef struct {
+    int32_t kernel;          /* star_kernel; STAR_KERNEL_AUTO = the library chooses                    */
+    int32_t reserved;        /* must be 0                                                              */
+    int64_t queue_threshold; /* shards of at least this many elements are processed by long-lived
+                                workgroups that claim tiles (1024 consecutive elements of every
+                                buffer) in address order from a work queue; shorter ones get a fixed
+                                assignment, which starts faster.  0 = default (16 Mi elements);
+                                1 = always the queue; negative: STAR_ERR_SHAPE                         */
+} star_options;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is
  * members[offsets[u] .. offsets[u+1]).  (Worker group: Section 1 item (4).) */
@@ -128,6 +156,22 @@ typedef struct {
  *                      gradient for this shard, P elements of grad_dtype.
  *                      Rows no group references are never read (may be NULL).
  *   norms_out        : device float[U], or NULL when norms are not wanted.
+ * Precision of the norms.  For a stream of two or more updates they are derived
+ * from the Gram matrix of the rows, n_u^2 = c_u^T Gamma c_u (one pass whatever
+ * U is).  That form is as accurate as its terms are free of cancellation: the
+ * relative error of n_u is at most 1e-7 * kappa_u,
+ *     kappa_u = (sum_w |c_{u,w}| ||g_w||)^2 / n_u^2,
+ * which lies between 1 and y_u for non-negative weights on rows that are not
+ * anti-correlated (every weighting of the paper; observed errors are 1e-7 and
+ * less there) and grows without bound when a group's weighted sum nearly
+ * cancels.  With coefficients of both signs (STAR_W_EXPLICIT) the library
+ * therefore takes the norms from direct sums of gbar_u^2 in a pass of its
+ * own (error 1e-6 or less, one more read of the rows); star_options.kernel =
+ * STAR_KERNEL_SEQ forces that direct form for any stream.
+ * Non-finite gradient values propagate: params and momentum of an element turn
+ * non-finite when a member of any group holds inf or NaN there (inf may come
+ * out as NaN), and norms_out[u] is non-finite exactly for the groups with such
+ * a member.
  */
 star_status star_group_update(float *params, float *momentum, const void *const *grad_rows,
                               star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
@@ -210,12 +254,29 @@ star_status star_group_reduce(void *const *out_rows, star_dtype out_dtype, const
 star_status star_plan_affine(int32_t W, const star_updates *upd, const star_hparams *hp, double M[4], double *B);
 
 /*
- * Host-only: which evaluation star_group_update would use for this stream on
- * fp32 rows (STAR_KERNEL_SEQ or STAR_KERNEL_AFFINE), and optionally the fused
- * multiply-adds per element of each (either pointer may be NULL).
+ * Host-only: what star_group_update (update = 1) or star_group_norms
+ * (update = 0) would launch for this call, decided by the same code that
+ * launches it; buffers are taken to be 16-byte aligned.
  */
-star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hparams *hp, int32_t want_norms,
-                             int32_t *kernel_out, double *fma_seq, double *fma_affine);
+typedef struct {
+    int32_t kernel;       /* star_kernel of the main kernel: STAR_KERNEL_SEQ (step-by-step), STAR_KERNEL_AFFINE
+                             (collapsed map; Gram matrix behind the norms, if any, in vector registers) or
+                             STAR_KERNEL_AFFINE_MFMA (collapsed map, Gram matrix on the matrix cores)       */
+    int32_t grad_dtype;   /* the star_dtype asked about                                                     */
+    int32_t rows_used;    /* gradient rows referenced by at least one group (only these are read)           */
+    int32_t rows_padded;  /* row count the kernel is instantiated for (extra rows carry zero coefficients)  */
+    int32_t queue_order;  /* 1: tiles claimed from the work queue, 0: fixed assignment                       */
+    int32_t launches;     /* launches of the main kernel the stream is split into (1 unless step-by-step)   */
+    int32_t finishing_launches; /* small kernels after the main one (norm reduction, norms from the Gram matrix) */
+    int32_t tables_inline;      /* 1: group tables travel in the kernel arguments, 0: staged through the workspace
+                                   (the collapsed map without norms needs no tables at all and reports 1)   */
+    double fma_seq;       /* fused multiply-adds per element of the step-by-step evaluation                 */
+    double fma_affine;    /* ... and of the collapsed one (vector-register Gram counted as FMAs)            */
+} star_plan_info;
+
+star_status star_plan_choice(int64_t P, int32_t W, star_dtype grad_dtype, const star_updates *upd,
+                             const star_hparams *hp, int32_t update, int32_t want_norms,
+                             const star_options *opt, star_plan_info *info);
 
 /*
  * Gram matrix of the gradient rows, Gamma[a][b] = sum_j g_a[j] g_b[j], the
@@ -228,6 +289,24 @@ star_status star_plan_choice(int32_t W, const star_updates *upd, const star_hpar
  */
 star_status star_group_gram(const void *const *grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
                             double *gram_out, void *hip_stream);
+
+/*
+ * The entry points above with per-call options (star_options; NULL = defaults).
+ * star_group_update_opt covers star_group_update (publish == NULL) and
+ * star_group_update_publish.  Everything else as documented above.
+ */
+star_status star_group_update_opt(float *params, float *momentum, const void *const *grad_rows,
+                                  star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
+                                  const star_hparams *hp, float *norms_out, void *publish,
+                                  star_dtype publish_dtype, const star_options *opt, void *hip_stream);
+star_status star_group_norms_opt(const void *const *grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                                 const star_updates *upd, int32_t wmode, float *norms_out,
+                                 const star_options *opt, void *hip_stream);
+star_status star_group_reduce_opt(void *const *out_rows, star_dtype out_dtype, const void *const *grad_rows,
+                                  star_dtype grad_dtype, int64_t P, int32_t W, const star_updates *upd,
+                                  int32_t wmode, float *norms_out, const star_options *opt, void *hip_stream);
+star_status star_group_gram_opt(const void *const *grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                                double *gram_out, const star_options *opt, void *hip_stream);
 
 /*
  * Host-only: gradient noise scale from the Gram matrix of W workers' gradients
@@ -310,27 +389,11 @@ star_status star_select_mode_ar(int32_t N, const double *iter_time, const double
                                 const double *wait_candidates, int32_t *removed_out, double *wait_out,
                                 double *time_out, double *time_table);
 
-/* Force an evaluation for later calls of this process (default AUTO; the
- * environment variable STAR_KERNEL=auto|seq|affine|affine_mfma sets the initial value). */
-star_status star_set_kernel(int32_t kernel);
-
-/*
- * How the workgroups of a kernel get their tiles (a tile is 1024 consecutive
- * elements of every buffer).  Shards of at least `elements` elements are
- * processed by one or two long-lived workgroups per compute unit that claim
- * tiles in address order from a small work queue in the workspace; shorter
- * shards get a fixed assignment, which starts faster.  Both compute the same
- * values; the matrix-core Gram kernel always uses the queue.  Default 16 Mi
- * (restored by elements = 0); 1 sends every shard through the queue, which is
- * what the tests do to check that path on small inputs.  STAR_ERR_SHAPE for a
- * negative value.
- */
-star_status star_set_queue_threshold(int64_t elements);
-
 /*
  * Host-only: the fixed first round of the work queue for a launch of
  * `workgroups` workgroups that claim `tiles_per_claim` tiles at a time (the
- * kernels use 3, or 5 when a thread moves less than 96 bytes per tile).
+ * kernels use 3; 5 when a thread moves less than 96 bytes per tile; 4 with the
+ * half-size workgroups of the collapsed update on 24 and more bf16 rows).
  * Workgroup b starts on tiles first_tile[b] .. first_tile[b] + count[b] - 1
  * (counts cycle 1, 2, .., tiles_per_claim: unequal on purpose, so that the
  * workgroups do not run in step); the tiles from *base on are handed out by

@@ -21,14 +21,17 @@ W_MEAN, W_STALE, W_EXPLICIT = 0, 1, 2
 _WMODES = {"mean": W_MEAN, "stale": W_STALE, "explicit": W_EXPLICIT}
 
 
+BUILD_FLAGS = ["-std=c11", "-O3", "-ffp-contract=off"]
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  No -march flags: the library may be built
     on one host and run on another.  -ffp-contract=off keeps the fp32 stepwise
-    mode free of fused multiply-adds."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra",
-             "-o", _LIB, _SRC, "-lm"])
+    mode free of fused multiply-adds; no fast-math, so the optimisation level
+    does not change a result."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
+                                                                        os.path.getmtime(__file__)):
+        subprocess.check_call(["gcc"] + BUILD_FLAGS + ["-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 

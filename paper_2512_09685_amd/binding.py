@@ -39,6 +39,25 @@ class _HParams(ctypes.Structure):
                 ("wmode", ctypes.c_int32), ("scale_lr_by_group", ctypes.c_int32)]
 
 
+class _Options(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("reserved", ctypes.c_int32), ("queue_threshold", ctypes.c_int64)]
+
+
+class _PlanInfo(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("rows_used", ctypes.c_int32),
+                ("rows_padded", ctypes.c_int32), ("queue_order", ctypes.c_int32), ("launches", ctypes.c_int32),
+                ("finishing_launches", ctypes.c_int32), ("tables_inline", ctypes.c_int32),
+                ("fma_seq", ctypes.c_double), ("fma_affine", ctypes.c_double)]
+
+
+def _options(kernel, queue_threshold):
+    """star_options for a call, or None when the caller left both at their defaults (the plain entry
+    point is called then)."""
+    if kernel is None and queue_threshold is None:
+        return None
+    return _Options(int(kernel or 0), 0, int(queue_threshold or 0))
+
+
 _lib = None
 
 
@@ -69,13 +88,19 @@ def load_library():
     lib.star_plan_affine.restype = ctypes.c_int
     lib.star_plan_affine.argtypes = [i32, vp, vp, vp, vp]
     lib.star_plan_choice.restype = ctypes.c_int
-    lib.star_plan_choice.argtypes = [i32, vp, vp, i32, vp, vp, vp]
-    lib.star_set_kernel.restype = ctypes.c_int
-    lib.star_set_kernel.argtypes = [i32]
+    lib.star_plan_choice.argtypes = [i64, i32, ctypes.c_int, vp, vp, i32, i32, vp, vp]
+    lib.star_group_update_opt.restype = ctypes.c_int
+    lib.star_group_update_opt.argtypes = [vp, vp, vp, ctypes.c_int, i64, i32, vp, vp, vp, vp, ctypes.c_int, vp, vp]
+    lib.star_group_norms_opt.restype = ctypes.c_int
+    lib.star_group_norms_opt.argtypes = [vp, ctypes.c_int, i64, i32, vp, i32, vp, vp, vp]
+    lib.star_group_reduce_opt.restype = ctypes.c_int
+    lib.star_group_reduce_opt.argtypes = [vp, ctypes.c_int, vp, ctypes.c_int, i64, i32, vp, i32, vp, vp, vp]
+    lib.star_group_gram.restype = ctypes.c_int
+    lib.star_group_gram.argtypes = [vp, ctypes.c_int, i64, i32, vp, vp]
+    lib.star_group_gram_opt.restype = ctypes.c_int
+    lib.star_group_gram_opt.argtypes = [vp, ctypes.c_int, i64, i32, vp, vp, vp]
     lib.star_plan_claims.restype = ctypes.c_int
     lib.star_plan_claims.argtypes = [i32, i32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
-    lib.star_set_queue_threshold.restype = ctypes.c_int
-    lib.star_set_queue_threshold.argtypes = [ctypes.c_int64]
     lib.star_workspace_bytes.restype = ctypes.c_size_t
     lib.star_workspace_bytes.argtypes = [i64, i32, i32]
     lib.star_last_error.restype = ctypes.c_char_p
@@ -153,11 +178,13 @@ def _stream_handle(stream):
 
 def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStream, *, lr: float, momentum_coef: float,
                       weight_decay: float = 0.0, wmode="mean", scale_lr_by_group: bool = False, norms_out=None,
-                      stream=None) -> None:
+                      stream=None, kernel=None, queue_threshold=None) -> None:
     """U group updates of one shard, in place, enqueued on ``stream``
     (default: torch's current stream).  ``params``/``momentum``: float32 CUDA
     tensors [P]; ``grad_rows``: W tensors [P] (float32 or bfloat16);
-    ``norms_out``: float32 CUDA tensor [U] or None."""
+    ``norms_out``: float32 CUDA tensor [U] or None.  ``kernel`` /
+    ``queue_threshold``: the fields of ``star_options`` (the call then goes
+    through ``star_group_update_opt``)."""
     lib = load_library()
     P = int(params.shape[0])
     if not (params.is_contiguous() and momentum.is_contiguous()) or momentum.shape[0] != P:
@@ -166,9 +193,15 @@ def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStre
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
     if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
         raise ValueError("norms_out must hold U floats")
-    _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
-                                 ctypes.byref(updates.c), ctypes.byref(hp),
-                                 None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
+    opt = _options(kernel, queue_threshold)
+    n_ptr = None if norms_out is None else norms_out.data_ptr()
+    if opt is None:
+        _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                     ctypes.byref(updates.c), ctypes.byref(hp), n_ptr, _stream_handle(stream)))
+    else:
+        _check(lib.star_group_update_opt(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                         ctypes.byref(updates.c), ctypes.byref(hp), n_ptr, None, F32,
+                                         ctypes.byref(opt), _stream_handle(stream)))
 
 
 def star_group_update_noalloc(params, momentum, grad_rows: Sequence, updates: UpdateStream, *, lr: float,
@@ -191,7 +224,8 @@ def star_group_update_noalloc(params, momentum, grad_rows: Sequence, updates: Up
 
 def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: UpdateStream, publish, *, lr: float,
                               momentum_coef: float, weight_decay: float = 0.0, wmode="mean",
-                              scale_lr_by_group: bool = False, norms_out=None, stream=None) -> None:
+                              scale_lr_by_group: bool = False, norms_out=None, stream=None, kernel=None,
+                              queue_threshold=None) -> None:
     """star_group_update that also writes the updated parameters into ``publish``
     (float32 or bfloat16 CUDA tensor [P]) in the same pass."""
     import torch
@@ -205,25 +239,38 @@ def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: Up
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
     if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
         raise ValueError("norms_out must hold U floats")
-    _check(lib.star_group_update_publish(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
-                                         ctypes.byref(updates.c), ctypes.byref(hp),
-                                         None if norms_out is None else norms_out.data_ptr(), publish.data_ptr(),
-                                         F32 if publish.dtype == torch.float32 else BF16, _stream_handle(stream)))
+    opt = _options(kernel, queue_threshold)
+    n_ptr = None if norms_out is None else norms_out.data_ptr()
+    pdt = F32 if publish.dtype == torch.float32 else BF16
+    if opt is None:
+        _check(lib.star_group_update_publish(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                             ctypes.byref(updates.c), ctypes.byref(hp), n_ptr, publish.data_ptr(),
+                                             pdt, _stream_handle(stream)))
+    else:
+        _check(lib.star_group_update_opt(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
+                                         ctypes.byref(updates.c), ctypes.byref(hp), n_ptr, publish.data_ptr(), pdt,
+                                         ctypes.byref(opt), _stream_handle(stream)))
 
 
-def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, wmode="mean", stream=None) -> None:
+def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, wmode="mean", stream=None,
+                     kernel=None, queue_threshold=None) -> None:
     lib = load_library()
     P = int(next(r for r in grad_rows if r is not None).shape[0])
     ptrs, dt = _rows(grad_rows, P)
     if norms_out.shape[0] < updates.U or not norms_out.is_contiguous():
         raise ValueError("norms_out must hold U floats")
-    _check(lib.star_group_norms(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c),
-                                _WMODES[wmode] if isinstance(wmode, str) else wmode, norms_out.data_ptr(),
-                                _stream_handle(stream)))
+    opt = _options(kernel, queue_threshold)
+    wm = _WMODES[wmode] if isinstance(wmode, str) else wmode
+    if opt is None:
+        _check(lib.star_group_norms(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c), wm, norms_out.data_ptr(),
+                                    _stream_handle(stream)))
+    else:
+        _check(lib.star_group_norms_opt(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c), wm,
+                                        norms_out.data_ptr(), ctypes.byref(opt), _stream_handle(stream)))
 
 
 def star_group_reduce(out_rows: Sequence, grad_rows: Sequence, updates: UpdateStream, *, wmode="mean", norms_out=None,
-                      stream=None) -> None:
+                      stream=None, kernel=None, queue_threshold=None) -> None:
     """out_rows[u] = weighted sum of group u's gradient rows (float32 or bfloat16
     CUDA tensors [P], one per group), enqueued on ``stream``."""
     import torch
@@ -235,9 +282,15 @@ def star_group_reduce(out_rows: Sequence, grad_rows: Sequence, updates: UpdateSt
     optrs, odt = _rows(out_rows, P)
     if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
         raise ValueError("norms_out must hold U floats")
-    _check(lib.star_group_reduce(optrs, odt, ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c),
-                                 _WMODES[wmode] if isinstance(wmode, str) else wmode,
-                                 None if norms_out is None else norms_out.data_ptr(), _stream_handle(stream)))
+    opt = _options(kernel, queue_threshold)
+    wm = _WMODES[wmode] if isinstance(wmode, str) else wmode
+    n_ptr = None if norms_out is None else norms_out.data_ptr()
+    if opt is None:
+        _check(lib.star_group_reduce(optrs, odt, ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c), wm, n_ptr,
+                                     _stream_handle(stream)))
+    else:
+        _check(lib.star_group_reduce_opt(optrs, odt, ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c), wm, n_ptr,
+                                         ctypes.byref(opt), _stream_handle(stream)))
 
 
 def star_plan_affine(W: int, updates: UpdateStream, *, lr: float, momentum_coef: float, weight_decay: float = 0.0,
@@ -251,19 +304,22 @@ def star_plan_affine(W: int, updates: UpdateStream, *, lr: float, momentum_coef:
     return M.reshape(2, 2), B[:2 * W].reshape(2, W)
 
 
-def star_plan_choice(W: int, updates: UpdateStream, *, lr: float, momentum_coef: float, weight_decay: float = 0.0,
-                     wmode="mean", scale_lr_by_group: bool = False, want_norms: bool = False):
-    """Host-only: (kernel, fma_seq, fma_affine)."""
+def star_plan_choice(P: int, W: int, grad_dtype, updates: UpdateStream, *, lr: float = 0.0, momentum_coef: float = 0.0,
+                     weight_decay: float = 0.0, wmode="mean", scale_lr_by_group: bool = False, update: bool = True,
+                     want_norms: bool = False, kernel=None, queue_threshold=None) -> dict:
+    """Host-only: what the library would launch for this call (the fields of
+    ``star_plan_info``).  ``grad_dtype``: "f32" | "bf16" or the dtype code."""
     lib = load_library()
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
-    k = ctypes.c_int32(0)
-    a, b = ctypes.c_double(0), ctypes.c_double(0)
-    _check(lib.star_plan_choice(W, ctypes.byref(updates.c), ctypes.byref(hp), int(want_norms), ctypes.byref(k),
-                                ctypes.byref(a), ctypes.byref(b)))
-    return k.value, a.value, b.value
+    dt = {"f32": F32, "bf16": BF16}.get(grad_dtype, grad_dtype)
+    info = _PlanInfo()
+    opt = _options(kernel, queue_threshold)
+    _check(lib.star_plan_choice(P, W, dt, ctypes.byref(updates.c), ctypes.byref(hp), int(bool(update)),
+                                int(bool(want_norms)), None if opt is None else ctypes.byref(opt), ctypes.byref(info)))
+    return {name: getattr(info, name) for name, _ in _PlanInfo._fields_}
 
 
-def star_group_gram(grad_rows: Sequence, gram_out, *, stream=None) -> None:
+def star_group_gram(grad_rows: Sequence, gram_out, *, stream=None, kernel=None, queue_threshold=None) -> None:
     """gram_out (float64 CUDA tensor [W, W]) = Gram matrix of the W gradient rows."""
     lib = load_library()
     P = int(grad_rows[0].shape[0])
@@ -271,9 +327,11 @@ def star_group_gram(grad_rows: Sequence, gram_out, *, stream=None) -> None:
     W = len(grad_rows)
     if gram_out.numel() != W * W or not gram_out.is_contiguous() or gram_out.element_size() != 8:
         raise ValueError("gram_out must be a contiguous float64 tensor of W*W elements")
-    lib.star_group_gram.restype = ctypes.c_int
-    _check(lib.star_group_gram(ptrs, ctypes.c_int(dt), ctypes.c_int64(P), ctypes.c_int32(W),
-                               ctypes.c_void_p(gram_out.data_ptr()), _stream_handle(stream)))
+    opt = _options(kernel, queue_threshold)
+    if opt is None:
+        _check(lib.star_group_gram(ptrs, dt, P, W, gram_out.data_ptr(), _stream_handle(stream)))
+    else:
+        _check(lib.star_group_gram_opt(ptrs, dt, P, W, gram_out.data_ptr(), ctypes.byref(opt), _stream_handle(stream)))
 
 
 def star_noise_scale(gram, batch_per_worker: float):
@@ -345,10 +403,6 @@ def star_select_mode_ar(iter_time, child_time, phi: float, batch_total: float, w
     return x.value, tw.value, ta.value, table
 
 
-def star_set_kernel(kernel: int) -> None:
-    _check(load_library().star_set_kernel(kernel))
-
-
 def star_plan_claims(workgroups: int, tiles_per_claim: int = 3):
     """(first_tile[G], count[G], base) of the work queue's fixed first round."""
     first = np.zeros(max(workgroups, 1), np.int64)
@@ -357,10 +411,6 @@ def star_plan_claims(workgroups: int, tiles_per_claim: int = 3):
     _check(load_library().star_plan_claims(workgroups, tiles_per_claim, first.ctypes.data, count.ctypes.data,
                                            ctypes.byref(base)))
     return first, count, int(base.value)
-
-
-def star_set_queue_threshold(elements: int) -> None:
-    _check(load_library().star_set_queue_threshold(elements))
 
 
 def star_workspace_bytes(P: int, W: int, U: int) -> int:

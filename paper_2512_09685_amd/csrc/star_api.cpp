@@ -3,7 +3,6 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
-#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -44,8 +43,27 @@ int initial_kernel_choice() {
     return STAR_KERNEL_AUTO;
 }
 
-std::atomic<int> g_kernel_choice{initial_kernel_choice()};
-std::atomic<int64_t> g_queue_min{star::kQueueMinElements};
+const int g_env_kernel = initial_kernel_choice();   // what STAR_KERNEL_AUTO means for calls that do not choose
+
+// The options of one call, resolved: never a process-wide state.
+struct Opts {
+    int kernel = STAR_KERNEL_AUTO;
+    int64_t queue_min = star::kQueueMinElements;
+};
+
+star_status resolve_options(const star_options* o, Opts* out) {
+    out->kernel = g_env_kernel;
+    out->queue_min = star::kQueueMinElements;
+    if (!o) return STAR_OK;
+    if (o->kernel != STAR_KERNEL_AUTO && o->kernel != STAR_KERNEL_SEQ && o->kernel != STAR_KERNEL_AFFINE &&
+        o->kernel != STAR_KERNEL_AFFINE_MFMA)
+        return set_err(STAR_ERR_KERNEL, "unknown kernel choice in star_options");
+    if (o->reserved != 0) return set_err(STAR_ERR_SHAPE, "star_options.reserved must be 0");
+    if (o->queue_threshold < 0) return set_err(STAR_ERR_SHAPE, "star_options.queue_threshold is negative");
+    if (o->kernel != STAR_KERNEL_AUTO) out->kernel = o->kernel;
+    if (o->queue_threshold > 0) out->queue_min = o->queue_threshold;
+    return STAR_OK;
+}
 
 // ---------------------------------------------------------------- workspace
 // A ring of slots.  One call uses one slot: a pinned host staging buffer and a
@@ -213,13 +231,61 @@ bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice) {
     return Wp > star::kFewRows;
 }
 
+// What a call launches: decided here, once, for run() and for star_plan_choice.
+struct Launch {
+    star::Route route = star::Route::Affine;
+    bool mfma = false;        // collapsed route: Gram matrix on the matrix cores
+    int Wp = 1;               // row count of the kernel instantiation
+    bool want_queue = false;  // the shard is long enough for queue order
+    bool queue_order = false; // the main kernel really takes its tiles from the queue (aligned buffers assumed)
+    bool seq_inline = false;  // step-by-step route: tables in the kernel arguments
+    int umax = 1;             // step-by-step route: updates per launch
+    int launches = 1;
+    int finishing = 0;
+    bool split_norms = false; // update by the collapsed map, norms by a separate direct pass (see decide)
+};
+
+Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_norms, int64_t P, const Opts& opt) {
+    Launch l;
+    l.route = star::choose_route(plan, grad_dtype == STAR_F32 ? 4 : 2, opt.kernel);
+    // Norms from the Gram matrix, n^2 = c^T Gamma c, lose digits when the terms of that sum cancel.  With
+    // the weightings of the paper (c >= 0) they cancel only if the rows themselves are anti-correlated;
+    // with caller-given coefficients of both signs they cancel as a rule (a difference of two similar
+    // rows).  Unless the caller forces an evaluation, such streams get their norms from the direct sums
+    // of gbar^2 (step-by-step kernel, norms only), in a pass of its own beside the collapsed update.
+    if (want_norms && plan.negative_coef && opt.kernel == STAR_KERNEL_AUTO && l.route == star::Route::Affine) {
+        if (update) l.split_norms = true;
+        else l.route = star::Route::Seq;
+    }
+    l.Wp = star::padded_rows(plan.Wc);
+    l.want_queue = P >= opt.queue_min;
+    if (l.route == star::Route::Affine) {
+        const bool gram = want_norms;
+        l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel);
+        l.queue_order = l.mfma || (l.want_queue && star::aff_takes_queue(gram, l.Wp));
+        l.launches = (update || gram) ? 1 : 0;
+        l.finishing = gram ? 2 : 0;
+    } else {
+        l.umax = star::seq_max_updates(l.Wp, want_norms);
+        l.seq_inline = star::tables_fit_inline(plan.U, l.Wp) && plan.U <= l.umax;
+        l.launches = (plan.U + l.umax - 1) / l.umax;
+        l.queue_order = l.want_queue && star::seq_takes_queue(std::min(plan.U, l.umax));
+        l.finishing = want_norms ? l.launches : 0;
+    }
+    return l;
+}
+
 // The shared body of star_group_update (update = true) and star_group_norms.  With `no_alloc` the
 // call works in the fixed device array of star_scratch.hip instead of a workspace slot and allocates
 // no device memory, pinned memory or event.
 star_status run(bool update, float* params, float* momentum, const void* const* grad_rows, int grad_dtype,
                 int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp, int32_t wmode,
-                float* norms_out, void* publish, int publish_dtype, void* hip_stream, bool no_alloc = false) {
+                float* norms_out, void* publish, int publish_dtype, const star_options* options, void* hip_stream,
+                bool no_alloc = false) {
     g_err.clear();
+    Opts opt;
+    star_status st = resolve_options(options, &opt);
+    if (st != STAR_OK) return st;
     if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
     if (no_alloc && upd->U > star::kScratchMaxUpdates)
         return set_err(STAR_ERR_SHAPE, "U=" + std::to_string(upd->U) + " is more than the " +
@@ -237,7 +303,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const bool want_norms = norms_out != nullptr;
     star::Plan plan;
     std::string msg;
-    star_status st = star::build_plan(W, upd, update ? hp : nullptr, wmode, want_norms, &plan, &msg);
+    st = star::build_plan(W, upd, update ? hp : nullptr, wmode, want_norms, &plan, &msg);
     if (st != STAR_OK) return set_err(st, msg);
     const int U = plan.U, Wc = plan.Wc;
     if (P > 0)
@@ -256,8 +322,18 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     if (st != STAR_OK) return st;
     const int grid_cap = star::kGridCap;
 
-    const star::Route route = star::choose_route(plan, grad_dtype == STAR_F32 ? 4 : 2, g_kernel_choice.load());
-    const int Wp = star::padded_rows(Wc);
+    const Launch how = decide(plan, grad_dtype, update, want_norms, P, opt);
+    if (how.split_norms) {
+        // the rows do not change during the call, so the norms may come first
+        const star_options direct = {STAR_KERNEL_SEQ, 0, opt.queue_min};
+        st = run(false, nullptr, nullptr, grad_rows, grad_dtype, P, W, upd, nullptr, hp->wmode, norms_out, nullptr, 0,
+                 &direct, hip_stream, no_alloc);
+        if (st != STAR_OK) return st;
+        return run(true, params, momentum, grad_rows, grad_dtype, P, W, upd, hp, 0, nullptr, publish, publish_dtype,
+                   options, hip_stream, no_alloc);
+    }
+    const star::Route route = how.route;
+    const int Wp = how.Wp;
 
     // rows in compact order; padding rows repeat the last row with zero coefficients
     star::RowPtrs rows;
@@ -269,8 +345,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
     // tables of the step-by-step kernel: in the kernel arguments when small and the whole stream fits in
     // one launch (a launch reads the inline tables from entry 0), else staged through the slot
-    const bool seq_inline = route != star::Route::Affine && star::tables_fit_inline(U, Wp) &&
-                            U <= star::seq_max_updates(Wp, want_norms);
+    const bool seq_inline = route != star::Route::Affine && how.seq_inline;
     star::InlineTables inl;
     if (seq_inline) {
         for (int u = 0; u < U; ++u) {
@@ -284,7 +359,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
     // a workspace slot only when something has to live in it (tables, norm partials)
     const TableLayout lay = table_layout(U, Wp);
-    const bool want_queue = P >= g_queue_min.load();
+    const bool want_queue = how.want_queue;
     const bool need_slot = need_seq_tables || need_gram_coef || want_norms || want_queue;
     std::unique_lock<std::mutex> lock(g_mu, std::defer_lock);
     Slot* slot = nullptr;
@@ -376,7 +451,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish_dtype = publish_dtype;
             a.partials = partials;
             a.queue = want_queue ? queue : nullptr;
-            const bool mfma = gram && gram_on_matrix_cores(Wp, grad_dtype, g_kernel_choice.load());
+            const bool mfma = how.mfma;
             if (mfma) a.queue = queue;   // that kernel always takes its tiles from the queue
             e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
                      : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);
@@ -394,7 +469,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     // step-by-step evaluation
     if (route == star::Route::Seq) {
         const bool seq_update = update;
-        const int umax = star::seq_max_updates(Wp, want_norms);
+        const int umax = how.umax;
         for (int u0 = 0; u0 < U; u0 += umax) {
             const int n = std::min(umax, U - u0);
             star::SeqArgs a;
@@ -427,8 +502,12 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
 
 // Body of star_group_reduce.
 star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* grad_rows, int grad_dtype, int64_t P,
-                       int32_t W, const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
+                       int32_t W, const star_updates* upd, int32_t wmode, float* norms_out,
+                       const star_options* options, void* hip_stream) {
     g_err.clear();
+    Opts opt;
+    star_status st = resolve_options(options, &opt);
+    if (st != STAR_OK) return st;
     if (!upd) return set_err(STAR_ERR_NULL, "updates struct is NULL");
     if (!grad_rows) return set_err(STAR_ERR_NULL, "grad_rows is NULL");
     if (!out_rows && upd->U > 0) return set_err(STAR_ERR_NULL, "out_rows is NULL");
@@ -438,7 +517,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
     const bool want_norms = norms_out != nullptr;
     star::Plan plan;
     std::string msg;
-    star_status st = star::build_plan(W, upd, nullptr, wmode, want_norms, &plan, &msg);
+    st = star::build_plan(W, upd, nullptr, wmode, want_norms, &plan, &msg);
     if (st != STAR_OK) return set_err(st, msg);
     const int U = plan.U, Wc = plan.Wc;
     if (P > 0) {
@@ -510,7 +589,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         a.vec_ok = vec_ok ? 1 : 0;
         a.norms = want_norms ? 1 : 0;
         a.partials = slot->partials;
-        a.queue = P >= g_queue_min.load() ? slot->queue : nullptr;
+        a.queue = P >= opt.queue_min ? slot->queue : nullptr;
         int grid = 0;
         hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
         if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
@@ -522,47 +601,13 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
     return STAR_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-star_status star_group_update(float* params, float* momentum, const void* const* grad_rows, star_dtype grad_dtype,
-                              int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
-                              float* norms_out, void* hip_stream) {
-    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, hip_stream);
-}
-
-star_status star_group_update_noalloc(float* params, float* momentum, const void* const* grad_rows,
-                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
-                                      const star_hparams* hp, float* norms_out, void* hip_stream) {
-    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, hip_stream,
-               true);
-}
-
-star_status star_group_update_publish(float* params, float* momentum, const void* const* grad_rows,
-                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
-                                      const star_hparams* hp, float* norms_out, void* publish,
-                                      star_dtype publish_dtype, void* hip_stream) {
-    if (!publish && P > 0) return set_err(STAR_ERR_NULL, "publish buffer is NULL");
-    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, publish,
-               (int)publish_dtype, hip_stream);
-}
-
-star_status star_group_norms(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
-                             const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
-    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, nullptr, 0,
-               hip_stream);
-}
-
-star_status star_group_reduce(void* const* out_rows, star_dtype out_dtype, const void* const* grad_rows,
-                              star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd, int32_t wmode,
-                              float* norms_out, void* hip_stream) {
-    return run_reduce(out_rows, (int)out_dtype, grad_rows, (int)grad_dtype, P, W, upd, wmode, norms_out, hip_stream);
-}
-
-star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
-                            double* gram_out, void* hip_stream) {
+// Body of star_group_gram.
+star_status run_gram(const void* const* grad_rows, int grad_dtype, int64_t P, int32_t W, double* gram_out,
+                     const star_options* options, void* hip_stream) {
     g_err.clear();
+    Opts opt;
+    star_status st = resolve_options(options, &opt);
+    if (st != STAR_OK) return st;
     if (!grad_rows || !gram_out) return set_err(STAR_ERR_NULL, "grad_rows or gram_out is NULL");
     if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
     if (W < 1 || W > star::kMaxGramW) return set_err(STAR_ERR_SHAPE, "the Gram matrix is built for 1 to 32 rows");
@@ -581,7 +626,7 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
         if (k < W && !aligned16(a.rows.p[k])) vec_ok = false;
     }
     int device = 0, num_cu = 1;
-    star_status st = device_info(&device, &num_cu);
+    st = device_info(&device, &num_cu);
     if (st != STAR_OK) return st;
     std::lock_guard<std::mutex> lock(g_mu);
     Slot* slot = nullptr;
@@ -593,10 +638,10 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     a.partials = slot->partials;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
-    const bool mfma = gram_on_matrix_cores(Wp, (int)grad_dtype, g_kernel_choice.load());
-    a.queue = (mfma || P >= g_queue_min.load()) ? slot->queue : nullptr;
-    hipError_t e = mfma ? star::launch_affine_mfma(Wp, (int)grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
-                        : star::launch_affine(Wp, (int)grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
+    const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel);
+    a.queue = (mfma || P >= opt.queue_min) ? slot->queue : nullptr;
+    hipError_t e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
+                        : star::launch_affine(Wp, grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");
     const int ng = Wp * (Wp + 1) / 2;
     double* gamma = slot->partials + (size_t)ng * grid;
@@ -605,6 +650,78 @@ star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype,
     e = star::launch_gram_unpack(gamma, Wp, W, gram_out, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram unpack kernel");
     return STAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+star_status star_group_update(float* params, float* momentum, const void* const* grad_rows, star_dtype grad_dtype,
+                              int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
+                              float* norms_out, void* hip_stream) {
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, nullptr,
+               hip_stream);
+}
+
+star_status star_group_update_noalloc(float* params, float* momentum, const void* const* grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
+                                      const star_hparams* hp, float* norms_out, void* hip_stream) {
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, nullptr, 0, nullptr,
+               hip_stream, true);
+}
+
+star_status star_group_update_publish(float* params, float* momentum, const void* const* grad_rows,
+                                      star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd,
+                                      const star_hparams* hp, float* norms_out, void* publish,
+                                      star_dtype publish_dtype, void* hip_stream) {
+    if (!publish && P > 0) return set_err(STAR_ERR_NULL, "publish buffer is NULL");
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, publish,
+               (int)publish_dtype, nullptr, hip_stream);
+}
+
+star_status star_group_update_opt(float* params, float* momentum, const void* const* grad_rows, star_dtype grad_dtype,
+                                  int64_t P, int32_t W, const star_updates* upd, const star_hparams* hp,
+                                  float* norms_out, void* publish, star_dtype publish_dtype, const star_options* opt,
+                                  void* hip_stream) {
+    return run(true, params, momentum, grad_rows, (int)grad_dtype, P, W, upd, hp, 0, norms_out, publish,
+               (int)publish_dtype, opt, hip_stream);
+}
+
+star_status star_group_norms(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                             const star_updates* upd, int32_t wmode, float* norms_out, void* hip_stream) {
+    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, nullptr, 0,
+               nullptr, hip_stream);
+}
+
+star_status star_group_norms_opt(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                                 const star_updates* upd, int32_t wmode, float* norms_out, const star_options* opt,
+                                 void* hip_stream) {
+    return run(false, nullptr, nullptr, grad_rows, (int)grad_dtype, P, W, upd, nullptr, wmode, norms_out, nullptr, 0,
+               opt, hip_stream);
+}
+
+star_status star_group_reduce(void* const* out_rows, star_dtype out_dtype, const void* const* grad_rows,
+                              star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd, int32_t wmode,
+                              float* norms_out, void* hip_stream) {
+    return run_reduce(out_rows, (int)out_dtype, grad_rows, (int)grad_dtype, P, W, upd, wmode, norms_out, nullptr,
+                      hip_stream);
+}
+
+star_status star_group_reduce_opt(void* const* out_rows, star_dtype out_dtype, const void* const* grad_rows,
+                                  star_dtype grad_dtype, int64_t P, int32_t W, const star_updates* upd, int32_t wmode,
+                                  float* norms_out, const star_options* opt, void* hip_stream) {
+    return run_reduce(out_rows, (int)out_dtype, grad_rows, (int)grad_dtype, P, W, upd, wmode, norms_out, opt,
+                      hip_stream);
+}
+
+star_status star_group_gram(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                            double* gram_out, void* hip_stream) {
+    return run_gram(grad_rows, (int)grad_dtype, P, W, gram_out, nullptr, hip_stream);
+}
+
+star_status star_group_gram_opt(const void* const* grad_rows, star_dtype grad_dtype, int64_t P, int32_t W,
+                                double* gram_out, const star_options* opt, void* hip_stream) {
+    return run_gram(grad_rows, (int)grad_dtype, P, W, gram_out, opt, hip_stream);
 }
 
 star_status star_noise_scale(int32_t W, const double* gram, double batch_per_worker, double* grad_sq,
@@ -647,18 +764,42 @@ star_status star_plan_affine(int32_t W, const star_updates* upd, const star_hpar
     return STAR_OK;
 }
 
-star_status star_plan_choice(int32_t W, const star_updates* upd, const star_hparams* hp, int32_t want_norms,
-                             int32_t* kernel_out, double* fma_seq, double* fma_affine) {
+star_status star_plan_choice(int64_t P, int32_t W, star_dtype grad_dtype, const star_updates* upd,
+                             const star_hparams* hp, int32_t update, int32_t want_norms, const star_options* options,
+                             star_plan_info* info) {
     g_err.clear();
-    if (!hp) return set_err(STAR_ERR_NULL, "hp is NULL");
+    Opts opt;
+    star_status st = resolve_options(options, &opt);
+    if (st != STAR_OK) return st;
+    if (!info) return set_err(STAR_ERR_NULL, "info is NULL");
+    if (update && !hp) return set_err(STAR_ERR_NULL, "hp is NULL");
+    if (P < 0) return set_err(STAR_ERR_SHAPE, "P is negative");
+    if (grad_dtype != STAR_F32 && grad_dtype != STAR_BF16) return set_err(STAR_ERR_DTYPE, "unknown gradient dtype");
+    if (!update && !want_norms) return set_err(STAR_ERR_NULL, "neither the update nor the norms are asked for");
     star::Plan plan;
     std::string msg;
-    star_status st = star::build_plan(W, upd, hp, 0, want_norms != 0, &plan, &msg);
+    st = star::build_plan(W, upd, update ? hp : nullptr, hp ? hp->wmode : 0, want_norms != 0, &plan, &msg);
     if (st != STAR_OK) return set_err(st, msg);
-    const star::Route r = star::choose_route(plan, 4, g_kernel_choice.load());
-    if (kernel_out) *kernel_out = r == star::Route::Seq ? STAR_KERNEL_SEQ : STAR_KERNEL_AFFINE;
-    if (fma_seq) *fma_seq = plan.fma_seq;
-    if (fma_affine) *fma_affine = plan.fma_affine;
+    Launch how = decide(plan, (int)grad_dtype, update != 0, want_norms != 0, P, opt);
+    if (how.split_norms) {   // the update as if without norms, plus the launches of the direct norm pass
+        Opts direct = opt;
+        direct.kernel = STAR_KERNEL_SEQ;
+        const Launch norms = decide(plan, (int)grad_dtype, false, true, P, direct);
+        how = decide(plan, (int)grad_dtype, true, false, P, opt);
+        how.launches += norms.launches;
+        how.finishing += norms.finishing;
+    }
+    std::memset(info, 0, sizeof *info);
+    info->kernel = how.route == star::Route::Seq ? STAR_KERNEL_SEQ : (how.mfma ? STAR_KERNEL_AFFINE_MFMA : STAR_KERNEL_AFFINE);
+    info->grad_dtype = (int32_t)grad_dtype;
+    info->rows_used = plan.Wc;
+    info->rows_padded = how.Wp;
+    info->queue_order = how.queue_order ? 1 : 0;
+    info->launches = how.launches;
+    info->finishing_launches = how.finishing;
+    info->tables_inline = how.route == star::Route::Seq ? (how.seq_inline ? 1 : 0) : (want_norms ? 0 : 1);
+    info->fma_seq = plan.fma_seq;
+    info->fma_affine = plan.fma_affine;
     return STAR_OK;
 }
 
@@ -674,22 +815,6 @@ star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_
         count[b] = f.n;
         *base = (int64_t)f.base;
     }
-    return STAR_OK;
-}
-
-star_status star_set_queue_threshold(int64_t elements) {
-    g_err.clear();
-    if (elements < 0) return set_err(STAR_ERR_SHAPE, "the threshold is negative");
-    g_queue_min.store(elements == 0 ? star::kQueueMinElements : elements);
-    return STAR_OK;
-}
-
-star_status star_set_kernel(int32_t kernel) {
-    g_err.clear();
-    if (kernel != STAR_KERNEL_AUTO && kernel != STAR_KERNEL_SEQ && kernel != STAR_KERNEL_AFFINE &&
-        kernel != STAR_KERNEL_AFFINE_MFMA)
-        return set_err(STAR_ERR_KERNEL, "unknown kernel choice");
-    g_kernel_choice.store(kernel);
     return STAR_OK;
 }
 

@@ -102,6 +102,13 @@ struct SeqArgs {
     TileQueue* queue;      // device, zeroed; null: fixed assignment of tiles to workgroups
 };
 
+// Which launches take their tiles from the queue when the caller hands one in (the matrix-core kernel
+// always does): the step-by-step kernel for one or two updates (longer streams are bound by arithmetic
+// and keep the fixed assignment with as many waves as fit), the collapsed one unless it carries the
+// register-heavy Gram accumulators of more than kFewRows rows.
+inline bool seq_takes_queue(int updates_in_launch) { return updates_in_launch <= 2; }
+inline bool aff_takes_queue(bool gram, int Wp) { return !gram || Wp <= kFewRows; }
+
 // Largest number of updates one launch of the step-by-step kernel accepts
 // (bounded by the LDS tables and, with norms, the per-thread accumulators).
 int seq_max_updates(int Wp, bool norms);

@@ -194,6 +194,11 @@ template <int W, bool UPDATE, bool NORMS>
 __device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float (&v)[4],
                                           const float* s_coef, const float* s_lr, const uint32_t* s_mask,
                                           double* s_nacc, const int U, const float mu, const float wd) {
+    // Running compensation of p over the updates of a launch (Kahan): p moves by increments far smaller
+    // than itself, and U plain roundings of p would add up like sqrt(U) half-ulps (U = 300: beyond 1e-6).
+    // With the lost low part carried along, p ends within an ulp of the exactly accumulated value for any
+    // U.  A single update keeps the plain fused step (nothing to carry).
+    float lost[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int u = 0; u < U; ++u) {
         const uint32_t m = __builtin_amdgcn_readfirstlane(s_mask[u]);
         float gb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -217,7 +222,14 @@ __device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float
             for (int k = 0; k < 4; ++k) {
                 const float d = __builtin_fmaf(wd, p[k], gb[k]);   // d = gbar + wd p
                 v[k] = __builtin_fmaf(mu, v[k], d);                // v = mu v + d
-                p[k] = __builtin_fmaf(-lr, v[k], p[k]);            // p = p - lr v
+                if (U == 1) {
+                    p[k] = __builtin_fmaf(-lr, v[k], p[k]);        // p = p - lr v
+                } else {
+                    const float y = __builtin_fmaf(-lr, v[k], -lost[k]);   // the step, less what the last sum dropped
+                    const float t = p[k] + y;
+                    lost[k] = (t - p[k]) - y;
+                    p[k] = t;
+                }
             }
         }
     }
@@ -381,6 +393,9 @@ __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __rest
             ++a;
         }
         const int b = a + rem;
+        // rows outside the group take no part: a non-finite entry of a worker that is not a member (0 * inf)
+        // must not reach this group's norm
+        if (c[a] == 0.0 || c[b] == 0.0) continue;
         const double t = c[a] * c[b] * gamma[e];
         s += (a == b) ? t : 2.0 * t;
     }
@@ -390,7 +405,9 @@ __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __rest
         if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0 && u < U) norms_out[u] = (float)sqrt(s_part[0] > 0.0 ? s_part[0] : 0.0);
+    // a tiny negative sum (rounding of a quadratic form that is zero) gives 0; a non-finite one stays
+    // non-finite, so that a bad gradient report shows in the norms of the groups it is part of
+    if (threadIdx.x == 0 && u < U) norms_out[u] = (float)sqrt(s_part[0] < 0.0 && s_part[0] > -1e300 ? 0.0 : s_part[0]);
 }
 
 // Packed upper triangle (row-major, a <= b) -> full symmetric W x W matrix; a zero
@@ -430,7 +447,7 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
     // one or two updates are bound by memory and take their tiles from the queue; longer streams are bound
     // by arithmetic and latency and keep the fixed assignment with as many waves as fit
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = a.queue && a.vec_ok && a.U <= 2;
+    const bool queued = a.queue && a.vec_ok && seq_takes_queue(a.U);
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes)
                               : pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap, thread_bytes, 4);
     *grid_out = g.grid;
@@ -445,15 +462,18 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
     // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = (!GRAM || W <= kFewRows) && a.queue && a.vec_ok;
+    const bool queued = aff_takes_queue(GRAM, W) && a.queue && a.vec_ok;
     Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes)
                         : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     // 24 and more bf16 rows: twice as many workgroups of half the size (tiles of 1 KB per row) measured
     // 3-4 % faster (32 rows, 138 M elements: 1.92 against 1.98 ms); with 16 rows the same is 15 % slower,
-    // and fp32 rows do not care
+    // and fp32 rows do not care.  With these half-size tiles claims of 4 (4 KB of every row, 8 KB of the
+    // state) are the fastest: 1-4 % ahead of 3 on every box and shard length tried (32 rows, 138 M
+    // elements: 1.81 against 1.89 ms; 24 rows 1.43 against 1.53 ms), 5 to 12 fall off again.
     if (queued && std::is_same<R, RowBf16x4>::value && W >= 24) {
         g.threads = kBlock / 2;
         g.grid = g.span_g = std::min(2 * g.grid, grid_cap);
+        g.claim = 4;
     }
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(g.threads), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,

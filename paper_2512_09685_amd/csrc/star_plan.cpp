@@ -42,6 +42,7 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
 
     plan->W = W;
     plan->U = U;
+    plan->negative_coef = false;
     plan->mu = hp ? (double)hp->momentum : 0.0;
     plan->wd = hp ? (double)hp->weight_decay : 0.0;
 
@@ -99,6 +100,7 @@ star_status build_plan(int32_t W, const star_updates* upd, const star_hparams* h
                 c = a / (double)y;
             }
             const int32_t k = compact_of[upd->members[m]];
+            if (c < 0.0) plan->negative_coef = true;
             plan->coef[(size_t)u * Wc + k] = c;
             plan->mask[u] |= 1u << k;
         }

@@ -26,6 +26,7 @@ struct Plan {
     std::vector<uint32_t> mask;
     std::vector<double> lr;
     std::vector<int32_t> ysize;
+    bool negative_coef = false;   // some coefficient is below zero (possible with STAR_W_EXPLICIT only)
 
     double mu = 0, wd = 0;
 

@@ -9,14 +9,26 @@ import paper_2512_09685_amd as star
 TOL = {"f32": 1e-6, "bf16": 4e-3}   # max |x-ref| / (|ref| + RMS(ref)), per gradient dtype
 
 
+_TILE_ORDER = {"queue_threshold": None}
+
+
 @pytest.fixture(autouse=True, params=["fixed", "queue"])
 def tile_order(request):
     """Runs every test of a module that imports it twice: with the fixed assignment of tiles to
     workgroups and with tiles claimed from the work queue (which the library itself only uses
-    from 16 Mi elements on), so that the small, fully checked cases cover both."""
-    star.star_set_queue_threshold(1 if request.param == "queue" else 1 << 62)
+    from 16 Mi elements on), so that the small, fully checked cases cover both.  The tests pass
+    the setting to every call as a per-call option: ``**opts()``."""
+    _TILE_ORDER["queue_threshold"] = 1 if request.param == "queue" else 1 << 62
     yield request.param
-    star.star_set_queue_threshold(0)
+    _TILE_ORDER["queue_threshold"] = None
+
+
+def opts(kernel=None):
+    """Per-call options of the running test: the fixture's tile order and, if given, a forced kernel."""
+    d = dict(_TILE_ORDER)
+    if kernel is not None:
+        d["kernel"] = kernel
+    return d
 
 
 def to_dev_rows(rows_np):
@@ -55,15 +67,11 @@ def rand_rows(rng, W, P, dtype, std=1e-2):
 def gpu_update(p0, v0, rows_np, offs, mem, *, kernel=star.KERNEL_AUTO, want_norms=False, staleness=None, coeff=None,
                lr_per_update=None, dev_rows=None, **hp):
     """Runs star_group_update on copies of p0, v0; returns numpy (p, v, norms)."""
-    star.star_set_kernel(kernel)
-    try:
-        p = torch.from_numpy(np.array(p0, dtype=np.float32)).cuda()
-        v = torch.from_numpy(np.array(v0, dtype=np.float32)).cuda()
-        rows = dev_rows if dev_rows is not None else to_dev_rows(rows_np)
-        us = star.UpdateStream(offs, mem, staleness, coeff, lr_per_update)
-        norms = torch.full((max(us.U, 1),), -1.0, dtype=torch.float32, device="cuda") if want_norms else None
-        star.star_group_update(p, v, rows, us, norms_out=norms, **hp)
-        torch.cuda.synchronize()
-        return p.cpu().numpy(), v.cpu().numpy(), (None if norms is None else norms.cpu().numpy()[:us.U])
-    finally:
-        star.star_set_kernel(star.KERNEL_AUTO)
+    p = torch.from_numpy(np.array(p0, dtype=np.float32)).cuda()
+    v = torch.from_numpy(np.array(v0, dtype=np.float32)).cuda()
+    rows = dev_rows if dev_rows is not None else to_dev_rows(rows_np)
+    us = star.UpdateStream(offs, mem, staleness, coeff, lr_per_update)
+    norms = torch.full((max(us.U, 1),), -1.0, dtype=torch.float32, device="cuda") if want_norms else None
+    star.star_group_update(p, v, rows, us, norms_out=norms, **opts(kernel), **hp)
+    torch.cuda.synchronize()
+    return p.cpu().numpy(), v.cpu().numpy(), (None if norms is None else norms.cpu().numpy()[:us.U])

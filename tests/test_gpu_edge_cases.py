@@ -1,0 +1,205 @@
+"""GPU parity on the degenerate inputs the header makes promises about: non-finite gradients, gradient
+rows that alias each other, group averages that nearly cancel, and per-call options used by several
+host threads at once."""
+import threading
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_09685_amd as star
+from oracle import star_oracle as so
+from gpu_util import TOL, gpu_update, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = {"auto": None, "seq": star.KERNEL_SEQ, "affine": star.KERNEL_AFFINE, "mfma": star.KERNEL_AFFINE_MFMA}
+
+
+def masked_err(x, ref):
+    """max_rel_err over the elements that are finite in the reference."""
+    m = np.isfinite(ref)
+    return so.max_rel_err(np.asarray(x)[m], np.asarray(ref)[m]) if m.any() else 0.0
+
+
+@pytest.mark.parametrize("kname", ["seq", "affine", "mfma", "auto"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_non_finite_gradients_propagate_like_the_oracle(kname, dtype):
+    """+inf, -inf and NaN at known positions of two workers' rows.  Params and momentum are non-finite
+    exactly where the oracle's are; the norm of a group is non-finite exactly when the group contains
+    one of the two workers; everything else matches to the usual tolerance.  A third worker that no
+    group references holds NaN everywhere and must not matter."""
+    rng = np.random.default_rng(41)
+    W, P, U = 7, 9001, 9
+    rows32 = [(rng.standard_normal(P) * 1e-2).astype(np.float32) for _ in range(W)]
+    rows32[2][[5, 1024, 4097]] = [np.inf, -np.inf, np.nan]
+    rows32[4][[5, 7000, P - 1]] = [-np.inf, np.inf, np.nan]      # element 5: +inf and -inf meet in groups with both
+    rows32[6][:] = np.nan                                       # never referenced
+    if dtype == "bf16":
+        rows = [torch.from_numpy(r).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy() for r in rows32]
+    else:
+        rows = rows32
+    # groups over workers 0..5: some with worker 2, some with 4, some with both, some with neither
+    groups = [[0, 1], [2], [0, 4, 5], [2, 4], [1, 3, 5], [0, 1, 2, 3, 4, 5], [3], [4, 0], [5, 1, 3]]
+    offs = np.cumsum([0] + [len(g) for g in groups]).astype(np.int32)
+    mem = np.concatenate(groups).astype(np.int32)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3)
+    with np.errstate(all="ignore"):
+        ep, ev, en = so.group_update(p0, v0, rows, offs, mem, want_norms=True, **hp)
+    p, v, n = gpu_update(p0, v0, rows, offs, mem, want_norms=True, kernel=KERNELS[kname], **hp)
+    assert np.array_equal(np.isfinite(p), np.isfinite(ep)), "params: finiteness differs from the oracle"
+    assert np.array_equal(np.isfinite(v), np.isfinite(ev)), "momentum: finiteness differs from the oracle"
+    assert int((~np.isfinite(ep)).sum()) == 5               # elements 5, 1024, 4097, 7000, P-1 and no other
+    tol = TOL[dtype]
+    assert masked_err(p, ep) <= tol and masked_err(v, ev) <= tol
+    bad = np.array([bool({2, 4} & set(g)) for g in groups])
+    assert np.array_equal(~np.isfinite(en), bad)            # the oracle itself: bad exactly for those groups
+    assert np.array_equal(~np.isfinite(n), bad), (kname, n)
+    good = ~bad
+    assert np.max(np.abs(n[good] - en[good]) / en[good]) <= tol
+
+
+@pytest.mark.parametrize("kname", ["seq", "affine", "mfma", "auto"])
+def test_gradient_rows_may_alias_each_other(kname):
+    """Several entries of grad_rows point at the same buffer (two workers reporting the same gradient)."""
+    rng = np.random.default_rng(42)
+    W, P, U = 6, 70001, 8
+    base = rand_rows(rng, 3, P, "f32")
+    which = [0, 1, 0, 2, 1, 0]                               # worker -> buffer
+    rows = [base[k] for k in which]
+    dev_base = to_dev_rows(base)
+    dev_rows = [dev_base[k] for k in which]
+    assert dev_rows[0].data_ptr() == dev_rows[2].data_ptr() == dev_rows[5].data_ptr()
+    offs, mem, st = rand_stream(rng, W, U, stale=3)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = np.zeros(P, np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, staleness=st, want_norms=True, **hp)
+    p, v, n = gpu_update(p0, v0, None, offs, mem, staleness=st, want_norms=True, kernel=KERNELS[kname],
+                         dev_rows=dev_rows, **hp)
+    assert so.max_rel_err(p, ep) <= 1e-6 and so.max_rel_err(v, ev) <= 1e-6
+    assert np.max(np.abs(n - en) / en) <= 1e-6
+    # aggregation and Gram matrix on the same aliased rows
+    outs = [torch.zeros(P, device="cuda") for _ in range(U)]
+    star.star_group_reduce(outs, dev_rows, star.UpdateStream(offs, mem, st), wmode="stale", **opts())
+    g = torch.zeros((W, W), dtype=torch.float64, device="cuda")
+    star.star_group_gram(dev_rows, g, **opts())
+    torch.cuda.synchronize()
+    eo = so.group_reduce(rows, offs, mem, wmode="stale", staleness=st)
+    assert max(so.max_rel_err(outs[u].cpu().numpy(), eo[u]) for u in range(U)) <= 1e-6
+    eg = so.gram(rows)
+    assert np.max(np.abs(g.cpu().numpy() - eg) / np.sqrt(np.outer(np.diag(eg), np.diag(eg)))) <= 1e-6
+
+
+def condition(rows32, offs, mem, coef):
+    """kappa_u = (sum_w |c_w| ||g_w||)^2 / ||sum_w c_w g_w||^2 of every group, from float64 copies of the rows."""
+    R = [np.asarray(r, np.float64) for r in rows32]
+    out = []
+    for u in range(len(offs) - 1):
+        ids, c = mem[offs[u]:offs[u + 1]], coef[offs[u]:offs[u + 1]]
+        gbar = sum(cw * R[w] for w, cw in zip(ids, c))
+        out.append(sum(abs(cw) * np.linalg.norm(R[w]) for w, cw in zip(ids, c)) ** 2 / float(gbar @ gbar))
+    return np.array(out)
+
+
+def test_signed_coefficients_take_the_direct_norm_route():
+    """Caller-given coefficients of both signs on nearly identical rows: the group 'average' is a small
+    difference of large rows.  The library takes such norms from the direct sums of gbar^2 (not from the
+    Gram matrix, whose quadratic form would cancel), and they hold the ordinary tolerance."""
+    rng = np.random.default_rng(43)
+    W, P = 4, 300007
+    g = (rng.standard_normal(P) * 1e-2).astype(np.float32)
+    rows = [(g + (rng.standard_normal(P) * 1e-5).astype(np.float32)) for _ in range(W)]
+    offs = np.array([0, 2, 4, 8], np.int32)
+    mem = np.array([0, 1, 2, 3, 0, 1, 2, 3], np.int32)
+    cf = np.array([1, -1, 0.5, -0.5, 1, -1, 1, -1], np.float32)
+    us = star.UpdateStream(offs, mem, None, cf)
+    c = star.star_plan_choice(P, W, "f32", us, lr=0.1, momentum_coef=0.9, wmode="explicit", want_norms=True)
+    assert c["kernel"] == star.KERNEL_AFFINE and c["launches"] == 2      # collapsed update + one direct norm pass
+    kappa = condition(rows, offs, mem, cf)
+    assert kappa.min() > 1e5                                            # the quadratic form would lose 5 digits
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)   # momentum on the scale of the rows: the state is judged
+    hp = dict(lr=0.1, momentum_coef=0.9, weight_decay=1e-4, wmode="explicit")   # against that scale, the norms on their own
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, coeff=cf, want_norms=True, **hp)
+    p, v, n = gpu_update(p0, v0, rows, offs, mem, coeff=cf, want_norms=True, **hp)
+    e_n = float(np.max(np.abs(n - en) / en))
+    print(f"signed coefficients: kappa {kappa.min():.3g}..{kappa.max():.3g}, norm err {e_n:.3g}", flush=True)
+    assert so.max_rel_err(p, ep) <= 1e-6 and so.max_rel_err(v, ev) <= 1e-6 and e_n <= 1e-6
+    # norms alone take the same route
+    n2 = torch.zeros(3, device="cuda")
+    star.star_group_norms(to_dev_rows(rows), us, n2, wmode="explicit", **opts())
+    torch.cuda.synchronize()
+    assert np.max(np.abs(n2.cpu().numpy() - en) / en) <= 1e-6
+
+
+@pytest.mark.parametrize("kname", ["affine", "mfma", "auto", "seq"])
+def test_anticorrelated_rows_hold_the_documented_norm_bound(kname):
+    """g_1 = -g_0 + small noise under plain mean weights: the group average nearly cancels although every
+    coefficient is positive.  The header's bound for norms that come from the Gram matrix: relative error
+    at most 1e-7 * kappa_u (kappa_u as computed above; 1..y_u for ordinary groups).  The direct route
+    (seq) is not subject to it and holds 1e-6."""
+    rng = np.random.default_rng(44)
+    W, P = 4, 200003
+    g0 = (rng.standard_normal(P) * 1e-2).astype(np.float32)
+    rows = [g0, (-g0 + (rng.standard_normal(P) * 1e-4).astype(np.float32)),
+            (rng.standard_normal(P) * 1e-2).astype(np.float32), (rng.standard_normal(P) * 1e-2).astype(np.float32)]
+    offs = np.array([0, 2, 4, 8], np.int32)
+    mem = np.array([0, 1, 2, 3, 0, 1, 2, 3], np.int32)
+    coef = np.concatenate([np.full(2, 0.5), np.full(2, 0.5), np.full(4, 0.25)])
+    kappa = condition(rows, offs, mem, coef)
+    en = so.group_norms(rows, offs, mem)
+    n = torch.zeros(3, device="cuda")
+    star.star_group_norms(to_dev_rows(rows), star.UpdateStream(offs, mem), n, **opts(KERNELS[kname]))
+    torch.cuda.synchronize()
+    err = np.abs(n.cpu().numpy() - en) / en
+    print(f"anti-correlated rows {kname}: kappa {np.round(kappa, 1).tolist()}, norm err {err.tolist()}", flush=True)
+    assert kappa[0] > 1e4 and kappa[1] < 4
+    if kname == "seq":
+        assert err.max() <= 1e-6
+    else:
+        assert np.all(err <= 1e-7 * kappa)
+        assert err[1] <= 1e-6 and err[2] <= 1e-6 * max(1.0, kappa[2] / 4)
+
+
+def test_two_threads_with_different_options():
+    """Two host threads call the library at the same time with different per-call options (one forces
+    the step-by-step kernel and the queue, the other the collapsed kernel and the fixed assignment);
+    each must get exactly what it gets alone: there is no process-wide setting to trample on."""
+    rng = np.random.default_rng(45)
+    W, P, U = 8, 300007, 6
+    rows = rand_rows(rng, W, P, "f32")
+    drows = to_dev_rows(rows)
+    offs, mem, st = rand_stream(rng, W, U, stale=3)
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+    settings = [dict(kernel=star.KERNEL_SEQ, queue_threshold=1), dict(kernel=star.KERNEL_AFFINE, queue_threshold=1 << 62)]
+
+    def run_one(o, out, reps):
+        stream = torch.cuda.Stream()
+        p = torch.from_numpy(p0).cuda()
+        v = torch.zeros(P, device="cuda")
+        n = torch.zeros(U, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            star.star_group_update(p, v, drows, star.UpdateStream(offs, mem, st), norms_out=n, stream=stream, **o, **hp)
+        stream.synchronize()
+        out.append((p.cpu().numpy(), v.cpu().numpy(), n.cpu().numpy()))
+
+    alone = []
+    for o in settings:
+        r = []
+        run_one(o, r, 8)
+        alone.append(r[0])
+    assert not np.array_equal(alone[0][0], alone[1][0])      # the two evaluations round differently: the options matter
+    together = [[], []]
+    threads = [threading.Thread(target=run_one, args=(o, together[i], 8)) for i, o in enumerate(settings)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for a, b in zip(alone, together):
+        for x, y in zip(a, b[0]):
+            assert np.array_equal(x, y)

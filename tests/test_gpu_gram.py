@@ -6,7 +6,7 @@ import torch
 
 import paper_2512_09685_amd as star
 from oracle import star_oracle as so
-from gpu_util import rand_rows, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+from gpu_util import opts, rand_rows, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -20,12 +20,9 @@ def test_gram_matrix(dtype, W, P, mfma):
     rows = rand_rows(rng, W, P, dtype)
     ref = so.gram(rows)
     out = torch.full((W, W), -1.0, dtype=torch.float64, device="cuda")
-    star.star_set_kernel(star.KERNEL_AFFINE_MFMA if mfma else star.KERNEL_AFFINE)   # matrix cores / vector registers
-    try:
-        star.star_group_gram(to_dev_rows(rows), out)
-        torch.cuda.synchronize()
-    finally:
-        star.star_set_kernel(star.KERNEL_AUTO)
+    kern = star.KERNEL_AFFINE_MFMA if mfma else star.KERNEL_AFFINE     # matrix cores / vector registers
+    star.star_group_gram(to_dev_rows(rows), out, **opts(kern))
+    torch.cuda.synchronize()
     got = out.cpu().numpy()
     assert np.array_equal(got, got.T)
     scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))          # |G_ab| <= sqrt(G_aa G_bb)
@@ -39,13 +36,13 @@ def test_gram_unaligned_rows_and_empty_shard():
     rows_big = rand_rows(rng, 4, 9002, "f32")
     d = [r[1:] for r in to_dev_rows(rows_big)]
     out = torch.zeros((4, 4), dtype=torch.float64, device="cuda")
-    star.star_group_gram(d, out)
+    star.star_group_gram(d, out, **opts())
     torch.cuda.synchronize()
     ref = so.gram([r[1:] for r in rows_big])
     assert np.max(np.abs(out.cpu().numpy() - ref) / np.max(ref)) <= 1e-6
     e = torch.empty(0, device="cuda")
     out = torch.full((2, 2), 5.0, dtype=torch.float64, device="cuda")
-    star.star_group_gram([e, e], out)
+    star.star_group_gram([e, e], out, **opts())
     torch.cuda.synchronize()
     assert torch.all(out == 0)
 
@@ -56,7 +53,7 @@ def test_noise_scale_from_device_gram():
     G = rng.standard_normal(P) * 0.02
     rows = [(G + rng.standard_normal(P) * sigma / np.sqrt(b)).astype(np.float32) for _ in range(W)]
     out = torch.zeros((W, W), dtype=torch.float64, device="cuda")
-    star.star_group_gram(to_dev_rows(rows), out)
+    star.star_group_gram(to_dev_rows(rows), out, **opts())
     torch.cuda.synchronize()
     g2, tr, phi = star.star_noise_scale(out.cpu().numpy(), b)
     eg2, etr, ephi = so.noise_scale(rows, b)

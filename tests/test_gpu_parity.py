@@ -8,7 +8,7 @@ import torch
 import paper_2512_09685_amd as star
 import workloads
 from oracle import star_oracle as so
-from gpu_util import TOL, gpu_update, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+from gpu_util import TOL, gpu_update, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,7 @@ def check(p, v, n, ep, ev, en, dtype, what=""):
     (1, 1, 1, True), (2, 3, 2, False), (4, 5, 10, True), (3, 1023, 7, True), (5, 1025, 12, False),
     (8, 4099, 24, True), (16, 70001, 16, True), (17, 33333, 9, True), (32, 50000, 12, False),
     (32, 20003, 6, True), (12, 600011, 20, True),
-    # short streams (the step-by-step kernel is queue-ordered up to 4 updates) and shards of more tiles than
+    # short streams (the step-by-step kernel is queue-ordered up to 2 updates) and shards of more tiles than
     # the first, fixed round of claims covers (256 or 512 workgroups x 2 tiles on average)
     (8, 300007, 2, True), (16, 1300003, 3, True), (16, 1300003, 16, True), (6, 1100000, 1, False),
     # streams that the step-by-step kernel splits over two launches although their tables are small
@@ -115,9 +115,10 @@ def test_run_to_run_bitwise_reproducible():
 
 
 def test_batch_split_carries_state():
-    """One call with U updates against two calls with U1 + U2: the step-by-step
-    kernel rounds after every update either way, so it must agree bit for bit;
-    the collapsed kernel agrees to rounding."""
+    """One call with U updates against two calls with U1 + U2.  Both evaluations agree to rounding: the
+    collapsed one rounds once per call, the step-by-step one carries the low part of the parameters
+    from update to update within a call and drops it at the call boundary (at most an ulp).  The
+    step-by-step norms do not depend on the state and must agree bit for bit."""
     rng = np.random.default_rng(7)
     W, P, U, k = 6, 50001, 14, 5
     rows = rand_rows(rng, W, P, "f32")
@@ -130,7 +131,7 @@ def test_batch_split_carries_state():
         pa, va, na = gpu_update(p0, v0, rows, offs[:k + 1], mem[:offs[k]], kernel=kern, **hp)
         pb, vb, nb = gpu_update(pa, va, rows, offs[k:] - offs[k], mem[offs[k]:], kernel=kern, **hp)
         if exact:
-            assert np.array_equal(p, pb) and np.array_equal(v, vb)
+            assert so.max_rel_err(pb, p) < 2e-7 and so.max_rel_err(vb, v) < 2e-7
             assert np.array_equal(n, np.concatenate([na, nb]))
         else:
             assert so.max_rel_err(pb, p) < 1e-6 and so.max_rel_err(vb, v) < 1e-6
@@ -148,8 +149,6 @@ def test_unaligned_buffers_give_identical_results(dtype):
     us = star.UpdateStream(offs, mem)
     hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3)
     for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
-        star.star_set_kernel(kern)
-        outs = []
         for shift in (0, 1):          # shift 1: every base pointer is off the 16-byte grid
             drows = [r[shift:shift + P].clone() if shift == 0 else r[shift:shift + P] for r in to_dev_rows(rows)]
             rows_same = [r[0:P] for r in rows] if shift == 0 else [r[1:1 + P] for r in rows]
@@ -158,12 +157,11 @@ def test_unaligned_buffers_give_identical_results(dtype):
             if shift == 0:
                 p, v = p.clone(), v.clone()
             n = torch.zeros(U, device="cuda")
-            star.star_group_update(p, v, drows, us, norms_out=n, **hp)
+            star.star_group_update(p, v, drows, us, norms_out=n, **opts(kern), **hp)
             torch.cuda.synchronize()
             ep, ev, en = so.group_update(p0[shift:shift + P], v0[shift:shift + P], rows_same, offs, mem,
                                          want_norms=True, **hp)
             check(p.cpu().numpy(), v.cpu().numpy(), n.cpu().numpy(), ep, ev, en, dtype, f"shift {shift}")
-        star.star_set_kernel(star.KERNEL_AUTO)
 
 
 def test_norms_entry_point_matches_update_norms():
@@ -175,11 +173,9 @@ def test_norms_entry_point_matches_update_norms():
         drows = to_dev_rows(rows)
         us = star.UpdateStream(offs, mem, st)
         for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AUTO, star.KERNEL_AFFINE_MFMA):
-            star.star_set_kernel(kern)
             n = torch.full((U,), -1.0, device="cuda")
-            star.star_group_norms(drows, us, n, wmode="stale")
+            star.star_group_norms(drows, us, n, wmode="stale", **opts(kern))
             torch.cuda.synchronize()
-            star.star_set_kernel(star.KERNEL_AUTO)
             err = np.max(np.abs(n.cpu().numpy() - en) / en)
             print(f"norms-only W={W} kern={kern} err={err:.3g}", flush=True)
             assert err <= TOL[dtype]
@@ -197,8 +193,9 @@ def test_long_stream_is_chunked():
     ep, ev, en = so.group_update(p0, v0, rows, offs, mem, **hp)
     for kern in (star.KERNEL_SEQ, star.KERNEL_AFFINE):
         p, v, n = gpu_update(p0, v0, rows, offs, mem, kernel=kern, **hp)
-        tol = 4e-6 if kern == star.KERNEL_SEQ else 1e-6      # 300 roundings of the state in the literal form
-        assert so.max_rel_err(p, ep) <= tol and so.max_rel_err(v, ev) <= tol
+        e_p, e_v = so.max_rel_err(p, ep), so.max_rel_err(v, ev)
+        print(f"U=300 kern={kern}: err p={e_p:.3g} v={e_v:.3g}", flush=True)
+        assert e_p <= 1e-6 and e_v <= 1e-6     # the literal form carries the low part of p from update to update
         np.testing.assert_allclose(n, en, rtol=1e-6)
 
 
@@ -237,12 +234,13 @@ def test_empty_cases_on_device():
     p = torch.ones(16, device="cuda")
     v = torch.ones(16, device="cuda")
     rows = [torch.ones(16, device="cuda")]
-    star.star_group_update(p, v, rows, star.UpdateStream([0], []), lr=0.1, momentum_coef=0.9)
+    star.star_group_update(p, v, rows, star.UpdateStream([0], []), lr=0.1, momentum_coef=0.9, **opts())
     torch.cuda.synchronize()
     assert torch.all(p == 1) and torch.all(v == 1)
     n = torch.full((2,), 5.0, device="cuda")
     e = torch.empty(0, device="cuda")
-    star.star_group_update(e, e, [e], star.UpdateStream([0, 1, 2], [0, 0]), lr=0.1, momentum_coef=0.9, norms_out=n)
+    star.star_group_update(e, e, [e], star.UpdateStream([0, 1, 2], [0, 0]), lr=0.1, momentum_coef=0.9, norms_out=n,
+                           **opts())
     torch.cuda.synchronize()
     assert n.tolist() == [0.0, 0.0]
 
@@ -269,7 +267,7 @@ def test_non_default_stream_and_back_to_back_calls():
     for call in range(4):
         offs, mem, st = streams[call]
         star.star_group_update(p, v, sets[call][1], star.UpdateStream(offs, mem, st), norms_out=norms[call],
-                               stream=s, **hp)
+                               stream=s, **opts(), **hp)
     s.synchronize()
     for call in range(4):
         offs, mem, st = streams[call]
@@ -310,6 +308,8 @@ def test_concurrent_host_threads_on_their_own_streams():
         jobs.append((rows, to_dev_rows(rows), offs, mem, st, p0))
     hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
 
+    call_opts = opts()      # read here: the worker threads below must not depend on the fixture's state
+
     def run_one(job, stream, out):
         rows, drows, offs, mem, st, p0 = job
         p = torch.from_numpy(p0).cuda()
@@ -317,7 +317,7 @@ def test_concurrent_host_threads_on_their_own_streams():
         n = torch.zeros(U, device="cuda")
         torch.cuda.synchronize()
         for _ in range(5):                       # several calls, so that the threads really overlap
-            star.star_group_update(p, v, drows, star.UpdateStream(offs, mem, st), norms_out=n, stream=stream, **hp)
+            star.star_group_update(p, v, drows, star.UpdateStream(offs, mem, st), norms_out=n, stream=stream, **call_opts, **hp)
         stream.synchronize()
         out.append((p.cpu().numpy(), v.cpu().numpy(), n.cpu().numpy()))
 
@@ -377,7 +377,7 @@ def test_interleaved_shards_shapes_and_kernels_without_host_sync():
         sh = shards[i]
         # a shard always uses the same stream, so its calls stay ordered; the two streams overlap
         star.star_group_update(sh["p"], sh["v"], sh["dev"], star.UpdateStream(offs, mem, st), norms_out=sh["n"],
-                               stream=s[i % 2], **hp)
+                               stream=s[i % 2], **opts(), **hp)
     for x in s:
         x.synchronize()
     for i, offs, mem, st in calls:

@@ -7,7 +7,7 @@ import torch
 
 import paper_2512_09685_amd as star
 from oracle import star_oracle as so
-from gpu_util import TOL, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+from gpu_util import TOL, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -26,23 +26,19 @@ def test_publish(pub, kern, W, P, U, dtype, norms, shift):
     v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
     hp = dict(lr=0.01, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
     us = star.UpdateStream(offs, mem, st)
-    star.star_set_kernel(kern)
-    try:
-        # reference run without publish
-        p_ref, v_ref = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
-        n_ref = torch.zeros(U, device="cuda") if norms else None
-        drows = to_dev_rows(rows)
-        star.star_group_update(p_ref, v_ref, drows, us, norms_out=n_ref, **hp)
-        # run with publish (optionally off the 16-byte grid)
-        p, v = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
-        n = torch.zeros(U, device="cuda") if norms else None
-        tdt = torch.float32 if pub == "f32" else torch.bfloat16
-        backing = torch.full((P + 8,), 3.0, dtype=tdt, device="cuda")
-        out = backing[shift:shift + P]
-        star.star_group_update_publish(p, v, drows, us, out, norms_out=n, **hp)
-        torch.cuda.synchronize()
-    finally:
-        star.star_set_kernel(star.KERNEL_AUTO)
+    # reference run without publish
+    p_ref, v_ref = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
+    n_ref = torch.zeros(U, device="cuda") if norms else None
+    drows = to_dev_rows(rows)
+    star.star_group_update(p_ref, v_ref, drows, us, norms_out=n_ref, **opts(kern), **hp)
+    # run with publish (optionally off the 16-byte grid)
+    p, v = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
+    n = torch.zeros(U, device="cuda") if norms else None
+    tdt = torch.float32 if pub == "f32" else torch.bfloat16
+    backing = torch.full((P + 8,), 3.0, dtype=tdt, device="cuda")
+    out = backing[shift:shift + P]
+    star.star_group_update_publish(p, v, drows, us, out, norms_out=n, **opts(kern), **hp)
+    torch.cuda.synchronize()
     assert torch.equal(p, p_ref) and torch.equal(v, v_ref)
     if norms:
         assert torch.equal(n, n_ref)
@@ -52,7 +48,7 @@ def test_publish(pub, kern, W, P, U, dtype, norms, shift):
     else:
         assert torch.equal(out.cpu(), p.cpu().to(torch.bfloat16))      # torch's CPU conversion rounds to nearest even
     ep, ev, _ = so.group_update(p0, v0, rows, offs, mem, staleness=st, **hp)
-    tol = 4e-3 if "bf16" in (pub, dtype) else (4e-6 if U > 100 and kern == star.KERNEL_SEQ else 1e-6)
+    tol = 4e-3 if "bf16" in (pub, dtype) else 1e-6
     assert so.max_rel_err(out.float().cpu().numpy(), ep) <= tol
 
 
@@ -69,7 +65,7 @@ def test_publish_special_values_round_to_nearest_even():
     rows = [torch.zeros(P, device="cuda")]
     out = torch.zeros(P, dtype=torch.bfloat16, device="cuda")
     # lr = 0: the update leaves params alone, publish converts them
-    star.star_group_update_publish(p, v, rows, star.UpdateStream([0, 1], [0]), out, lr=0.0, momentum_coef=0.0)
+    star.star_group_update_publish(p, v, rows, star.UpdateStream([0, 1], [0]), out, lr=0.0, momentum_coef=0.0, **opts())
     torch.cuda.synchronize()
     got = out.cpu().view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(got, expect)

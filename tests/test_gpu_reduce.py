@@ -6,7 +6,7 @@ import torch
 
 import paper_2512_09685_amd as star
 from oracle import star_oracle as so
-from gpu_util import TOL, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+from gpu_util import TOL, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -18,7 +18,7 @@ def run_reduce(rows_np, offs, mem, st, out_dtype, norms, P, wmode="stale", shift
     backing = [torch.full((P + 8,), 7.0, dtype=tdt, device="cuda") for _ in range(U)]
     outs = [b[shift:shift + P] for b in backing]
     n = torch.full((max(U, 1),), -1.0, device="cuda") if norms else None
-    star.star_group_reduce(outs, drows, star.UpdateStream(offs, mem, st), wmode=wmode, norms_out=n)
+    star.star_group_reduce(outs, drows, star.UpdateStream(offs, mem, st), wmode=wmode, norms_out=n, **opts())
     torch.cuda.synchronize()
     for b in backing:                                   # nothing written outside [shift, shift+P)
         assert torch.all(b[:shift] == 7.0) and torch.all(b[shift + P:] == 7.0)
@@ -63,14 +63,14 @@ def test_reduce_unaligned_outputs_and_rows(out_dtype):
     drows = [r[1:] for r in to_dev_rows(rows_big)]          # 4 bytes off the 16-byte grid
     tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
     outs = [torch.zeros(P + 3, dtype=tdt, device="cuda")[3:] for _ in range(U)]
-    star.star_group_reduce(outs, drows, star.UpdateStream(offs, mem, st), wmode="stale")
+    star.star_group_reduce(outs, drows, star.UpdateStream(offs, mem, st), wmode="stale", **opts())
     torch.cuda.synchronize()
     tol = 4e-3 if out_dtype == "bf16" else 1e-6
     for u in range(U):
         assert so.max_rel_err(outs[u].float().cpu().numpy(), eo[u]) <= tol
     # aligned and unaligned runs agree bit for bit
     outs2 = [torch.zeros(P, dtype=tdt, device="cuda") for _ in range(U)]
-    star.star_group_reduce(outs2, [r.clone() for r in drows], star.UpdateStream(offs, mem, st), wmode="stale")
+    star.star_group_reduce(outs2, [r.clone() for r in drows], star.UpdateStream(offs, mem, st), wmode="stale", **opts())
     torch.cuda.synchronize()
     for a, b in zip(outs, outs2):
         assert torch.equal(a, b)
@@ -86,14 +86,14 @@ def test_reduce_parent_aggregation_feeds_update():
     cf = np.ones(3, np.float32)
     eo = so.group_reduce(rows, offs, mem, wmode="explicit", coeff=cf)
     out = [torch.zeros(P, device="cuda")]
-    star.star_group_reduce(out, to_dev_rows(rows), star.UpdateStream(offs, mem, None, cf), wmode="explicit")
+    star.star_group_reduce(out, to_dev_rows(rows), star.UpdateStream(offs, mem, None, cf), wmode="explicit", **opts())
     torch.cuda.synchronize()
     assert so.max_rel_err(out[0].cpu().numpy(), eo[0]) <= 1e-6
     p0 = rng.standard_normal(P).astype(np.float32)
     p = torch.from_numpy(p0).cuda()
     v = torch.zeros(P, device="cuda")
     star.star_group_update(p, v, [out[0], to_dev_rows([rows[1]])[0]], star.UpdateStream([0, 2], [0, 1]),
-                           lr=0.1, momentum_coef=0.9)
+                           lr=0.1, momentum_coef=0.9, **opts())
     torch.cuda.synchronize()
     ep, ev, _ = so.group_update(p0, np.zeros(P, np.float32), [eo[0].astype(np.float32), rows[1]], [0, 2], [0, 1],
                                 lr=0.1, momentum_coef=0.9)
@@ -103,7 +103,7 @@ def test_reduce_parent_aggregation_feeds_update():
 def test_reduce_empty_cases():
     e = torch.empty(0, device="cuda")
     n = torch.full((1,), 3.0, device="cuda")
-    star.star_group_reduce([e], [e], star.UpdateStream([0, 1], [0]), norms_out=n)
-    star.star_group_reduce([], [torch.ones(4, device="cuda")], star.UpdateStream([0], []))
+    star.star_group_reduce([e], [e], star.UpdateStream([0, 1], [0]), norms_out=n, **opts())
+    star.star_group_reduce([], [torch.ones(4, device="cuda")], star.UpdateStream([0], []), **opts())
     torch.cuda.synchronize()
     assert n.item() == 0.0

@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
     assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_group_gram",
-            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_plan_claims", "star_set_kernel", "star_set_queue_threshold",
+            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_plan_claims", "star_group_update_opt", "star_group_norms_opt",
+            "star_group_reduce_opt", "star_group_gram_opt", "star_group_update_noalloc",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
     for n in names:
@@ -63,13 +64,30 @@ def test_empty_stream_and_empty_shard_are_no_ops():
     assert star.last_error() == ""
 
 
-def test_set_kernel_validation():
+def test_options_are_checked_before_anything_else():
+    """star_options of the *_opt entry points: unknown kernel, non-zero reserved field and a negative
+    threshold are rejected (with fake device addresses: nothing may be touched)."""
     lib = star.load_library()
-    assert lib.star_set_kernel(5) == 6
-    assert lib.star_set_kernel(0) == 0
-    assert lib.star_set_queue_threshold(-1) == 2
-    assert lib.star_set_queue_threshold(1) == 0
-    assert lib.star_set_queue_threshold(0) == 0
+    us = star.UpdateStream((0, 2), (0, 1))
+    hp = binding._HParams(0.1, 0.9, 0.0, 0, 0)
+    ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
+
+    def call(kernel=0, reserved=0, threshold=0, P=8):
+        o = binding._Options(kernel, reserved, threshold)
+        return lib.star_group_update_opt(0x1000, 0x2000, ptrs, 0, P, 4, ctypes.byref(us.c), ctypes.byref(hp), None,
+                                         None, 0, ctypes.byref(o), None)
+    assert call(kernel=5) == 6 and "kernel" in star.last_error()
+    assert call(kernel=-1) == 6
+    assert call(reserved=1) == 2
+    assert call(threshold=-1) == 2
+    assert call(kernel=3, threshold=1, P=0) == 0            # valid options, empty shard: a no-op
+    o = binding._Options(7, 0, 0)
+    n = (ctypes.c_float * 1)()
+    assert lib.star_group_norms_opt(ptrs, 0, 8, 4, ctypes.byref(us.c), 0, n, ctypes.byref(o), None) == 6
+    assert lib.star_group_reduce_opt(ptrs, 0, ptrs, 0, 8, 4, ctypes.byref(us.c), 0, None, ctypes.byref(o), None) == 6
+    assert lib.star_group_gram_opt(ptrs, 0, 8, 4, n, ctypes.byref(o), None) == 6
+    info = binding._PlanInfo()
+    assert lib.star_plan_choice(8, 4, 0, ctypes.byref(us.c), ctypes.byref(hp), 1, 0, ctypes.byref(o), ctypes.byref(info)) == 6
 
 
 @pytest.mark.parametrize("claim", [1, 3, 5])
@@ -140,15 +158,47 @@ def test_unused_rows_get_zero_coefficients():
     assert np.all(B[:, 1] == 0) and np.all(B[:, 3] == 0) and np.all(B[:, 0] != 0) and np.all(B[:, 2] != 0)
 
 
-def test_cost_model_prefers_literal_steps_for_one_update_and_collapse_for_many():
+def test_plan_choice_one_update_is_literal_many_are_collapsed():
     one = star.UpdateStream([0, 4], [0, 1, 2, 3])
-    k, fs, fa = star.star_plan_choice(4, one, lr=0.1, momentum_coef=0.9)
-    assert (k, fs, fa) == (star.KERNEL_SEQ, 7.0, 12.0)
+    c = star.star_plan_choice(1000, 4, "f32", one, lr=0.1, momentum_coef=0.9)
+    assert (c["kernel"], c["fma_seq"], c["fma_affine"]) == (star.KERNEL_SEQ, 7.0, 12.0)
+    assert c["launches"] == 1 and c["finishing_launches"] == 0 and c["tables_inline"] == 1 and c["queue_order"] == 0
+    assert star.star_plan_choice(1000, 4, "bf16", one, lr=0.1, momentum_coef=0.9)["kernel"] == star.KERNEL_AFFINE
     rng = np.random.default_rng(0)
     offs, mem, _ = _rand_stream(rng, 16, 64)
     many = star.UpdateStream(offs, mem)
-    k, fs, fa = star.star_plan_choice(16, many, lr=0.1, momentum_coef=0.9, want_norms=True)
-    assert k == star.KERNEL_AFFINE and fa == 36 + 136 and fs == len(mem) + 4 * 64
+    c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True)
+    assert c["kernel"] == star.KERNEL_AFFINE_MFMA and c["fma_affine"] == 36 + 136 and c["fma_seq"] == len(mem) + 4 * 64
+    assert c["queue_order"] == 1 and c["finishing_launches"] == 2      # the matrix-core kernel always takes the queue
+    c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True, kernel=star.KERNEL_AFFINE)
+    assert c["kernel"] == star.KERNEL_AFFINE and c["queue_order"] == 0
+    c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True, kernel=star.KERNEL_SEQ)
+    assert c["kernel"] == star.KERNEL_SEQ and c["launches"] == 3 and c["finishing_launches"] == 3 and c["tables_inline"] == 0
+
+
+def test_plan_choice_reports_the_kernels_of_the_five_workloads():
+    """What bench.py labels its roofline with: the library's own answer, for every workload as it is timed."""
+    import workloads
+    expect = {"tiny": (star.KERNEL_AFFINE, 4, 0), "resnet50": (star.KERNEL_AFFINE, 8, 1),
+              "bert_base": (star.KERNEL_AFFINE_MFMA, 16, 1), "vgg16": (star.KERNEL_AFFINE, 32, 1),
+              "bert_large": (star.KERNEL_AFFINE_MFMA, 16, 1)}
+    for name, (kernel, rows, queue) in expect.items():
+        wl = workloads.WORKLOADS[name]
+        s = workloads.make_update_stream(wl, 0, 0)
+        us = star.UpdateStream(s["offsets"], s["members"], s["staleness"])
+        c = star.star_plan_choice(wl.P, wl.W, wl.grad_dtype, us, lr=wl.lr, momentum_coef=wl.momentum,
+                                  weight_decay=wl.weight_decay, wmode=wl.wmode, want_norms=wl.norms)
+        assert (c["kernel"], c["rows_padded"], c["queue_order"]) == (kernel, rows, queue), (name, c)
+        assert c["rows_used"] == wl.W and c["launches"] == 1 and c["grad_dtype"] == (0 if wl.grad_dtype == "f32" else 1)
+        # a single update per call (every report applied on arrival): literal kernel on fp32 rows only
+        one = star.UpdateStream(s["offsets"][:2], s["members"][:s["offsets"][1]],
+                                None if s["staleness"] is None else s["staleness"][:s["offsets"][1]])
+        c1 = star.star_plan_choice(wl.P, wl.W, wl.grad_dtype, one, lr=wl.lr, momentum_coef=wl.momentum,
+                                   weight_decay=wl.weight_decay, wmode=wl.wmode, want_norms=False)
+        assert c1["kernel"] == (star.KERNEL_SEQ if wl.grad_dtype == "f32" else star.KERNEL_AFFINE)
+        # norms alone
+        cn = star.star_plan_choice(wl.P, wl.W, wl.grad_dtype, us, wmode=wl.wmode, update=False, want_norms=True)
+        assert cn["kernel"] == (star.KERNEL_AFFINE if wl.W <= 6 else star.KERNEL_AFFINE_MFMA)
 
 
 def test_workspace_bytes_is_modest():
@@ -268,8 +318,10 @@ def test_header_is_plain_c_and_links(tmp_path):
         '#include "star.h"\n#include <stdio.h>\nstatic int count;\n'
         "static void sink(void (*f)(void)) { if (f) ++count; }\n"
         "int main(void) {\n" + body + "\n"
-        "    if (star_set_kernel(99) != STAR_ERR_KERNEL) return 2;\n"
-        "    if (star_set_kernel(STAR_KERNEL_AUTO) != STAR_OK) return 3;\n"
+        "    { star_options o = {99, 0, 0}; star_plan_info info;\n"
+        "      if (star_plan_choice(8, 2, STAR_F32, 0, 0, 1, 0, &o, &info) != STAR_ERR_KERNEL) return 2; }\n"
+        "    { int64_t first[4]; int32_t cnt[4]; int64_t base;\n"
+        "      if (star_plan_claims(4, 3, first, cnt, &base) != STAR_OK || base != 7) return 3; }\n"
         '    printf("%d %s\\n", count, star_version());\n    return 0;\n}\n')
     exe = tmp_path / "abi"
     lib_dir = os.path.dirname(star.library_path())
