@@ -359,6 +359,7 @@ def main():
             "kernel": head["kernel"],
             "algorithmic_bytes_per_launch": head["bytes_per_launch"], "launch_ms": head["launch_ms"],
             "timed_launches": head["timed_launches"],
+            "launches_after_timed": FIRST_CALL_REPS * head["calls_per_step"],
             "device_copy_gbps": copy_gbps,
             "frac_of_device_copy": head["bytes_per_launch"] / (head["launch_ms"] * 1e-3) / 1e9 / copy_gbps,
             "note": "launch duration = HIP-event time of the timed region / launches; it includes the two small "

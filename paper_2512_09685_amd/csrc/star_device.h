@@ -319,12 +319,13 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
 inline int queue_workgroups_per_cu(int thread_bytes, bool writes_state) {
     return writes_state && thread_bytes >= 128 ? 1 : 2;
 }
-inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu, int thread_bytes) {
+inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu, int thread_bytes,
+                               Traffic traffic = Traffic::Update) {
     Geometry g;
     g.threads = kBlock;
     g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));
     g.span_k = 0x7fffffff;
-    g.claim = queue_claim(thread_bytes);
+    g.claim = queue_claim(thread_bytes, traffic);
     return g;
 }
 

@@ -30,7 +30,28 @@ struct TileQueue {
 // row and the state: 0.37 against 0.48 ms on 110 M elements), 6, 7 and 9 slower again.
 constexpr int kClaim = 3;
 constexpr int kClaimLight = 5;
-inline int queue_claim(int thread_bytes) { return thread_bytes < 96 ? kClaimLight : kClaim; }
+// What a launch does to memory decides how much work a claim should cover.  A claim's round trip to the
+// counter is hidden only if the workgroup has several microseconds of tiles left when it asks, and a
+// kernel that only reads gets through a tile much faster than one that also writes the state back:
+//   Update   reads the rows, reads and writes the state: 3 tiles, 5 when light (see above);
+//   ReadOnly the norms alone, the Gram matrix: about 200 KB per claim (16 bf16 rows, 32 KB a tile: 6 or 7
+//            tiles run 0.83-0.86 of the HBM peak against 0.68-0.71 with 3; 8 bf16 rows: 13 tiles 0.82
+//            against 0.61 with 5; 16 fp32 rows stay at 3);
+//   Reduce   reads the rows, writes one output row per group: about 140 KB per claim (16 bf16 rows: 4
+//            tiles 0.75 against 0.71 with 3; 16 fp32 rows: 2 tiles 0.74 against 0.72).
+enum class Traffic { Update, ReadOnly, Reduce };
+inline int queue_claim(int thread_bytes, Traffic traffic = Traffic::Update) {
+    const int tile = (thread_bytes < 1 ? 1 : thread_bytes) * kBlock;
+    if (traffic == Traffic::ReadOnly) {
+        const int c = (200 * 1024 + tile / 2) / tile;
+        return c < 3 ? 3 : (c > 16 ? 16 : c);
+    }
+    if (traffic == Traffic::Reduce) {
+        const int c = (140 * 1024 + tile / 2) / tile;
+        return c < 2 ? 2 : (c > 9 ? 9 : c);
+    }
+    return thread_bytes < 96 ? kClaimLight : kClaim;
+}
 
 // Shards shorter than this many elements keep the static mapping (and need no queue): with few tiles
 // per workgroup the claims' round trips show (1 Mi elements: 15 against 7.5 us); from 16 Mi on the

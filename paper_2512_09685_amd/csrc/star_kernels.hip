@@ -463,7 +463,8 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
     const bool queued = aff_takes_queue(GRAM, W) && a.queue && a.vec_ok;
-    Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes)
+    Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes,
+                                         UPDATE ? Traffic::Update : Traffic::ReadOnly)
                         : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);
     // 24 and more bf16 rows: twice as many workgroups of half the size (tiles of 1 KB per row) measured
     // 3-4 % faster (32 rows, 138 M elements: 1.92 against 1.98 ms); with 16 rows the same is 15 % slower,

@@ -147,7 +147,8 @@ hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* g
     auto kern = reduce_rows_kernel<W, R>;
     const size_t lds = reduce_lds_bytes(W, a.U, a.norms != 0);
     const bool queued = a.queue && a.vec_ok;
-    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(0, false), W * (int)sizeof(typename R::vec) + 16)
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(0, false),
+                                               W * (int)sizeof(typename R::vec) + 16, Traffic::Reduce)
                               : pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
                                               W * (int)sizeof(typename R::vec), 4);
     *grid_out = g.grid;
