@@ -223,11 +223,15 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
 // accumulators there and takes its tiles from the queue as well (norms on, 8 updates: 1 fp32 row 0.34
 // against 0.49 ms on 100 M elements, 4 rows 0.53 against 0.64; 1 bf16 row 0.59 against 0.66 ms on 200 M
 // elements; 6 rows equal, 7 and 8 rows 2-6 % behind).
-bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice) {
+// Without the update (norms alone, the Gram matrix alone) the state's 32 bytes per thread are missing and a
+// tile of few bf16 rows is so light that the vector-register form's per-chunk work shows: there the matrix
+// cores are ahead from 4 rows on (134 M elements, 4 / 5 / 6 bf16 rows: 0.57 / 0.65 / 0.71 of the HBM peak
+// against 0.48 / 0.55 / 0.43; fp32 rows: 0.46 / 0.56 / 0.65 against 0.80 / 0.82 / 0.65).
+bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
     if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
-    (void)grad_dtype;
+    if (!update && grad_dtype == STAR_BF16) return Wp >= 4;
     return Wp > star::kFewRows;
 }
 
@@ -261,7 +265,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     l.want_queue = P >= opt.queue_min;
     if (l.route == star::Route::Affine) {
         const bool gram = want_norms;
-        l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel);
+        l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update);
         l.queue_order = l.mfma || (l.want_queue && star::aff_takes_queue(gram, l.Wp));
         l.launches = (update || gram) ? 1 : 0;
         l.finishing = gram ? 2 : 0;
@@ -638,7 +642,7 @@ star_status run_gram(const void* const* grad_rows, int grad_dtype, int64_t P, in
     a.partials = slot->partials;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
-    const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel);
+    const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel, false);
     a.queue = (mfma || P >= opt.queue_min) ? slot->queue : nullptr;
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);

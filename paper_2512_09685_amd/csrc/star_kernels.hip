@@ -40,7 +40,10 @@ __device__ __forceinline__ void gram_step(float (&acc)[W * (W + 1) / 2], const f
         }
 }
 
-template <int W, class R, bool UPDATE, bool GRAM>
+// KCH: chunks a thread loads together per tile when the tiles come from the queue (a tile is then
+// KCH * 256 chunks).  More than one only for the Gram matrix alone on very few rows: a thread that loads 8
+// to 32 bytes per tile keeps too little in flight (1 fp32 row: 0.40 of the HBM peak), whatever the claim.
+template <int W, class R, bool UPDATE, bool GRAM, int KCH = 1>
 __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
@@ -128,14 +131,42 @@ __global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params,
         // code: tiles from the queue for long shards, a fixed assignment for short ones
         if (claim > 0) {
             queued = true;
-            const int64_t ntile = (nchunk + threads - 1) / threads;
-            for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
-                const int64_t c = tile * threads + threadIdx.x;
-                if (c < nchunk) {
-                    process(c);
-                    if constexpr (kFew) fold_now();
-                }
-            });
+            if constexpr (KCH > 1) {
+                static_assert(GRAM && !UPDATE, "several chunks per thread: Gram matrix alone");
+                const int64_t width = (int64_t)threads * KCH;
+                const int64_t ntile = (nchunk + width - 1) / width;
+                for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
+                    typename R::vec g[KCH][W];
+#pragma unroll
+                    for (int j = 0; j < KCH; ++j) {   // all loads of the tile first
+                        const int64_t c = tile * width + (int64_t)j * threads + threadIdx.x;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) g[j][w] = c < nchunk ? R::load(rows.p[w], c) : typename R::vec{};
+                    }
+#pragma unroll
+                    for (int j = 0; j < KCH; ++j) {   // a chunk beyond the end holds zeros and adds nothing
+                        static_for<0, VEC>([&](auto kc) {
+                            constexpr int K = decltype(kc)::value;
+                            float ge[W];
+                            static_for<0, W>([&](auto wc) {
+                                constexpr int Wi = decltype(wc)::value;
+                                ge[Wi] = R::template get<K>(g[j][Wi]);
+                            });
+                            gram_step<W>(acc, ge);
+                        });
+                        fold_now();   // per chunk, as with one chunk per tile: the sums do not depend on KCH
+                    }
+                });
+            } else {
+                const int64_t ntile = (nchunk + threads - 1) / threads;
+                for_each_claimed_tile(queue, ntile, claim, [&](const int64_t tile) {
+                    const int64_t c = tile * threads + threadIdx.x;
+                    if (c < nchunk) {
+                        process(c);
+                        if constexpr (kFew) fold_now();
+                    }
+                });
+            }
         }
     }
     if (!queued) {
@@ -459,10 +490,27 @@ hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_ou
 
 template <int W, class R, bool UPDATE, bool GRAM>
 hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
+    // the Gram matrix alone on very few rows: enough chunks per thread for about 64 bytes in flight
+    constexpr int kRowBytes = W * (int)sizeof(typename R::vec);
+    // (134 M elements, 1 / 2 / 3 fp32 rows: 0.69 / 0.78 / 0.79 of the HBM peak against 0.40 / 0.66 / 0.78 with one
+    // chunk; 1 / 2 / 3 bf16 rows with 4 / 4 / 2 chunks: 0.44 / 0.66 / 0.65 against 0.22 / 0.36 / 0.48)
+    constexpr int KCH = (GRAM && !UPDATE && W <= kFewRows && kRowBytes < 64)
+                            ? (kRowBytes <= 8 ? 8 : (kRowBytes <= 16 ? 4 : 2)) : 1;
+    const bool queued = aff_takes_queue(GRAM, W) && a.queue && a.vec_ok;
+    if constexpr (KCH > 1) {
+        if (queued) {
+            const int thread_bytes = kRowBytes * KCH;
+            const Geometry g = queue_geometry(num_cu, grid_cap, 2, thread_bytes, Traffic::ReadOnly);
+            *grid_out = g.grid;
+            hipLaunchKernelGGL((aff_kernel<W, R, UPDATE, GRAM, KCH>), dim3(g.grid), dim3(g.threads), 0, s, a.params,
+                               a.momentum, a.rows, a.cf, a.P, a.vec_ok, g.span_g, g.span_k, a.publish,
+                               a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue, g.claim);
+            return hipGetLastError();
+        }
+    }
     auto kern = aff_kernel<W, R, UPDATE, GRAM>;
     // long shards without the Gram accumulators: long-lived workgroups, tiles from the queue
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = aff_takes_queue(GRAM, W) && a.queue && a.vec_ok;
     Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes,
                                          UPDATE ? Traffic::Update : Traffic::ReadOnly)
                         : pick_geometry(a.P, R::VEC, a.vec_ok != 0, GRAM, num_cu, grid_cap);

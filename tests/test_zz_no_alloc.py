@@ -72,6 +72,28 @@ def test_noalloc_matches_group_update_two_calls_in_a_row(first, second):
             assert np.all(a > 0) and np.max(np.abs(a - b) / a) <= 1e-6
 
 
+def test_noalloc_signed_coefficients_two_passes():
+    """Coefficients of both signs: the norms come from a direct pass beside the collapsed update, so the
+    call uses the fixed array twice in a row (tables uploaded twice, queue cleared twice)."""
+    rng = np.random.default_rng(11)
+    W, P, U = 5, 17 * 1024 * 1024 + 77, 4
+    rows = _rows(rng, W, P, "f32")
+    offs, mem, _ = _stream(rng, W, U)
+    cf = rng.uniform(-1, 1, len(mem)).astype(np.float32)
+    us = star.UpdateStream(offs, mem, None, cf)
+    p0 = torch.from_numpy((rng.standard_normal(P) * 0.02).astype(np.float32)).cuda()
+    res = []
+    for fn in (star.star_group_update, star.star_group_update_noalloc):
+        p, v = p0.clone(), torch.zeros(P, device="cuda")
+        n = torch.full((U,), -1.0, device="cuda")
+        fn(p, v, rows, us, norms_out=n, lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="explicit")
+        torch.cuda.synchronize()
+        res.append((p, v, n))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    a, b = res[0][2].cpu().numpy(), res[1][2].cpu().numpy()
+    assert np.all(a > 0) and np.max(np.abs(a - b) / a) <= 1e-6
+
+
 def test_noalloc_against_the_oracle():
     rng = np.random.default_rng(7)
     W, P, U = 16, 123457, 20
