@@ -270,6 +270,11 @@ typedef struct {
     int32_t finishing_launches; /* small kernels after the main one (norm reduction, norms from the Gram matrix) */
     int32_t tables_inline;      /* 1: group tables travel in the kernel arguments, 0: staged through the workspace
                                    (the collapsed map without norms needs no tables at all and reports 1)   */
+    int32_t collapsed_update;   /* 1: params and momentum come from the one affine map of the stream.  Always so
+                                   with AFFINE and AFFINE_MFMA; with SEQ only for 17 to 32 fp32 rows, update
+                                   with norms and a short stream, where the step-by-step kernel walks the updates
+                                   for the norms alone (direct sums are cheaper there than the Gram matrix)   */
+    int32_t reserved;
     double fma_seq;       /* fused multiply-adds per element of the step-by-step evaluation                 */
     double fma_affine;    /* ... and of the collapsed one (vector-register Gram counted as FMAs)            */
 } star_plan_info;

@@ -47,6 +47,7 @@ class _PlanInfo(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("rows_used", ctypes.c_int32),
                 ("rows_padded", ctypes.c_int32), ("queue_order", ctypes.c_int32), ("launches", ctypes.c_int32),
                 ("finishing_launches", ctypes.c_int32), ("tables_inline", ctypes.c_int32),
+                ("collapsed_update", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("fma_seq", ctypes.c_double), ("fma_affine", ctypes.c_double)]
 
 

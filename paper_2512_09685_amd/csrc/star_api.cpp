@@ -247,6 +247,7 @@ struct Launch {
     int launches = 1;
     int finishing = 0;
     bool split_norms = false; // update by the collapsed map, norms by a separate direct pass (see decide)
+    bool collapsed_in_seq = false;   // step-by-step kernel walks the updates for the norms, applies the update as one map
 };
 
 Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_norms, int64_t P, const Opts& opt) {
@@ -263,6 +264,15 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     }
     l.Wp = star::padded_rows(plan.Wc);
     l.want_queue = P >= opt.queue_min;
+    // 17 to 32 fp32 rows, update with norms: the Gram matrix needs the fp32 matrix instructions (1536 flops per
+    // element, only partly hidden: 0.60-0.64 of the HBM peak).  A short stream gets its norms cheaper from the
+    // direct sums, y_u + 1 multiply-adds per update, in the same pass as the collapsed update.
+    if (update && want_norms && l.route == star::Route::Affine && !l.split_norms && opt.kernel == STAR_KERNEL_AUTO &&
+        grad_dtype == STAR_F32 && l.Wp > 16 && plan.U <= star::seq_max_updates(l.Wp, true) &&
+        plan.fma_seq - 3.0 * plan.U <= star::kDirectNormFmas) {
+        l.route = star::Route::Seq;
+        l.collapsed_in_seq = true;
+    }
     if (l.route == star::Route::Affine) {
         const bool gram = want_norms;
         l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update);
@@ -273,7 +283,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
         l.umax = star::seq_max_updates(l.Wp, want_norms);
         l.seq_inline = star::tables_fit_inline(plan.U, l.Wp) && plan.U <= l.umax;
         l.launches = (plan.U + l.umax - 1) / l.umax;
-        l.queue_order = l.want_queue && star::seq_takes_queue(std::min(plan.U, l.umax));
+        l.queue_order = l.want_queue && (l.collapsed_in_seq || star::seq_takes_queue(std::min(plan.U, l.umax)));
         l.finishing = want_norms ? l.launches : 0;
     }
     return l;
@@ -474,6 +484,18 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     if (route == star::Route::Seq) {
         const bool seq_update = update;
         const int umax = how.umax;
+        star::AffCoef cf;
+        std::memset(&cf, 0, sizeof cf);
+        if (how.collapsed_in_seq) {
+            cf.dp = (float)(plan.M[0] - 1.0);
+            cf.m01 = (float)plan.M[1];
+            cf.m10 = (float)plan.M[2];
+            cf.m11 = (float)plan.M[3];
+            for (int k = 0; k < Wc; ++k) {
+                cf.b0[k] = (float)plan.B[k];
+                cf.b1[k] = (float)plan.B[Wc + k];
+            }
+        }
         for (int u0 = 0; u0 < U; u0 += umax) {
             const int n = std::min(umax, U - u0);
             star::SeqArgs a;
@@ -484,6 +506,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.lr = seq_inline ? nullptr : reinterpret_cast<const float*>(d + lay.lr32) + u0;
             a.mask = seq_inline ? nullptr : reinterpret_cast<const uint32_t*>(d + lay.mask) + u0;
             a.inl = &inl;
+            a.cf = how.collapsed_in_seq ? &cf : nullptr;
             a.U = n;
             a.mu = (float)plan.mu;
             a.wd = (float)plan.wd;
@@ -802,6 +825,7 @@ star_status star_plan_choice(int64_t P, int32_t W, star_dtype grad_dtype, const 
     info->launches = how.launches;
     info->finishing_launches = how.finishing;
     info->tables_inline = how.route == star::Route::Seq ? (how.seq_inline ? 1 : 0) : (want_norms ? 0 : 1);
+    info->collapsed_update = (update && (how.route == star::Route::Affine || how.collapsed_in_seq)) ? 1 : 0;
     info->fma_seq = plan.fma_seq;
     info->fma_affine = plan.fma_affine;
     return STAR_OK;

@@ -33,7 +33,7 @@ constexpr int kClaimLight = 5;
 // What a launch does to memory decides how much work a claim should cover.  A claim's round trip to the
 // counter is hidden only if the workgroup has several microseconds of tiles left when it asks, and a
 // kernel that only reads gets through a tile much faster than one that also writes the state back:
-//   Update   reads the rows, reads and writes the state: 3 tiles, 5 when light (see above);
+//   Update   reads the rows, reads and writes the state: 3 tiles, 5 when light (see above), 2 when very heavy;
 //   ReadOnly the norms alone, the Gram matrix: about 200 KB per claim (16 bf16 rows, 32 KB a tile: 6 or 7
 //            tiles run 0.83-0.86 of the HBM peak against 0.68-0.71 with 3; 8 bf16 rows: 13 tiles 0.82
 //            against 0.61 with 5; 16 fp32 rows stay at 3);
@@ -50,6 +50,8 @@ inline int queue_claim(int thread_bytes, Traffic traffic = Traffic::Update) {
         const int c = (140 * 1024 + tile / 2) / tile;
         return c < 2 ? 2 : (c > 9 ? 9 : c);
     }
+    // very heavy tiles (20 to 32 fp32 rows: 90-140 KB a tile): two tiles a claim, 2-4 % ahead of three
+    if (thread_bytes >= 320) return 2;
     return thread_bytes < 96 ? kClaimLight : kClaim;
 }
 
@@ -113,6 +115,7 @@ struct SeqArgs {
     const float* lr;       // device [U]
     const uint32_t* mask;  // device [U]
     const InlineTables* inl;  // host; used when coef is null
+    const AffCoef* cf;     // host, or null; not null: the update is applied once, as this map (17-32 fp32 rows, update + norms)
     int32_t U;             // updates in this launch
     float mu, wd;
     int64_t P;
@@ -128,6 +131,9 @@ struct SeqArgs {
 // and keep the fixed assignment with as many waves as fit), the collapsed one unless it carries the
 // register-heavy Gram accumulators of more than kFewRows rows.
 inline bool seq_takes_queue(int updates_in_launch) { return updates_in_launch <= 2; }
+// Collapsed update with direct norms (step-by-step kernel's norm walk): for 17 to 32 fp32 rows, when the
+// stream's direct norm sums cost at most this many multiply-adds per element.
+constexpr double kDirectNormFmas = 320.0;
 inline bool aff_takes_queue(bool gram, int Wp) { return !gram || Wp <= kFewRows; }
 
 // Largest number of updates one launch of the step-by-step kernel accepts

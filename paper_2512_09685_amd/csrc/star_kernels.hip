@@ -266,7 +266,11 @@ __device__ __forceinline__ void seq_steps(float (&g)[W][4], float (&p)[4], float
     }
 }
 
-template <int W, class R, bool UPDATE, bool NORMS>
+// COLLAPSED (with UPDATE and NORMS): the norms are accumulated update by update as usual, the update itself is
+// applied once, as the affine map `cf` of the whole stream.  For wide fp32 rows with norms and a short stream:
+// the Gram matrix of 17 to 32 fp32 rows costs 1536 matrix flops per element whatever the stream, the direct
+// sums y_u + 1 multiply-adds per update.
+template <int W, class R, bool UPDATE, bool NORMS, bool COLLAPSED = false>
 __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const RowPtrs rows, const float* __restrict__ t_coef,
                                                      const float* __restrict__ t_lr,
@@ -275,8 +279,9 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
                                                      double* __restrict__ partials, TileQueue* __restrict__ queue,
-                                                     const int claim, const InlineTables inl) {
+                                                     const int claim, const InlineTables inl, const AffCoef cf) {
     static_assert(R::VEC == 4, "the step-by-step kernel works on 4-element chunks");
+    static_assert(!COLLAPSED || (UPDATE && NORMS), "the collapsed update rides on the norm walk");
     extern __shared__ double lds[];
     double* s_nacc = lds;
     double* s_wave = s_nacc + (NORMS ? U * kBlock : 0);
@@ -325,7 +330,18 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
                 g[Wi][K] = R::template get<K>(raw[Wi]);
             });
         });
-        seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        if constexpr (COLLAPSED) {
+            seq_steps<W, false, true>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+            static_for<0, 4>([&](auto kc) {
+                constexpr int K = decltype(kc)::value;
+                float ge[W];
+#pragma unroll
+                for (int w = 0; w < W; ++w) ge[w] = g[w][K];
+                aff_step<W>(p[K], v[K], ge, cf);
+            });
+        } else {
+            seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        }
         if constexpr (UPDATE) {
             f32x4 pv, vv;
 #pragma unroll
@@ -363,7 +379,15 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
             p[0] = params[j];
             v[0] = momentum[j];
         }
-        seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        if constexpr (COLLAPSED) {
+            seq_steps<W, false, true>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+            float ge[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) ge[w] = g[w][0];
+            aff_step<W>(p[0], v[0], ge, cf);
+        } else {
+            seq_steps<W, UPDATE, NORMS>(g, p, v, s_coef, s_lr, s_mask, s_nacc, U, mu, wd);
+        }
         if constexpr (UPDATE) {
             params[j] = p[0];
             momentum[j] = v[0];
@@ -471,20 +495,25 @@ size_t seq_lds_bytes(int W, int U, bool norms) {
            (norms ? sizeof(double) * ((size_t)(kBlock / 64) * U + (size_t)U * kBlock) : 0);
 }
 
-template <int W, class R, bool UPDATE, bool NORMS>
+template <int W, class R, bool UPDATE, bool NORMS, bool COLLAPSED = false>
 hipError_t launch_seq_t(const SeqArgs& a, int num_cu, int grid_cap, int* grid_out, hipStream_t s) {
-    auto kern = seq_kernel<W, R, UPDATE, NORMS>;
+    auto kern = seq_kernel<W, R, UPDATE, NORMS, COLLAPSED>;
     const size_t lds = seq_lds_bytes(W, a.U, NORMS);
     // one or two updates are bound by memory and take their tiles from the queue; longer streams are bound
     // by arithmetic and latency and keep the fixed assignment with as many waves as fit
     const int thread_bytes = W * (int)sizeof(typename R::vec) + (UPDATE ? 32 : 0);
-    const bool queued = a.queue && a.vec_ok && seq_takes_queue(a.U);
-    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(thread_bytes, UPDATE), thread_bytes)
+    // the collapsed form does so little arithmetic per update that it is bound by memory for any stream it is used for
+    const bool queued = a.queue && a.vec_ok && (COLLAPSED || seq_takes_queue(a.U));
+    // (the collapsed form's norm walk -- LDS reads and a wave-uniform branch per row and update -- needs a second
+    // workgroup per unit to hide under the memory time: 20 to 32 fp32 rows, 8 updates, 0.68-0.71 of the HBM peak with
+    // two against 0.43-0.45 with one)
+    const int per_cu = COLLAPSED ? 2 : queue_workgroups_per_cu(thread_bytes, UPDATE);
+    const Geometry g = queued ? queue_geometry(num_cu, grid_cap, per_cu, thread_bytes)
                               : pick_geometry(a.P, 4, a.vec_ok != 0, NORMS, num_cu, grid_cap, thread_bytes, 4);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.params, a.momentum, a.rows, a.coef, a.lr, a.mask,
                        a.U, a.mu, a.wd, a.P, a.vec_ok, g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0,
-                       a.partials, a.queue, g.claim, a.coef ? InlineTables() : *a.inl);
+                       a.partials, a.queue, g.claim, a.coef ? InlineTables() : *a.inl, a.cf ? *a.cf : AffCoef());
     return hipGetLastError();
 }
 
@@ -534,6 +563,13 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
 template <int W>
 hipError_t launch_seq_w(int dtype, bool update, bool norms, const SeqArgs& a, int num_cu, int grid_cap,
                         int* grid_out, hipStream_t s) {
+    if (a.cf) {   // collapsed update with direct norms: built for wide fp32 rows only
+        if constexpr (W > 16) {
+            if (dtype == STAR_F32 && update && norms)
+                return launch_seq_t<W, RowF32, true, true, true>(a, num_cu, grid_cap, grid_out, s);
+        }
+        return hipErrorInvalidValue;
+    }
     if (dtype == STAR_F32) {
         if (update && norms) return launch_seq_t<W, RowF32, true, true>(a, num_cu, grid_cap, grid_out, s);
         if (update) return launch_seq_t<W, RowF32, true, false>(a, num_cu, grid_cap, grid_out, s);

@@ -176,6 +176,33 @@ def test_plan_choice_one_update_is_literal_many_are_collapsed():
     assert c["kernel"] == star.KERNEL_SEQ and c["launches"] == 3 and c["finishing_launches"] == 3 and c["tables_inline"] == 0
 
 
+def test_plan_choice_wide_fp32_rows_with_norms():
+    """17 to 32 fp32 rows, update with norms: a short stream takes the collapsed update with direct norm sums
+    (step-by-step kernel, one launch, queue order on long shards), a long one the Gram matrix on the matrix cores;
+    bf16 rows, forced kernels and norms alone are not affected."""
+    rng = np.random.default_rng(1)
+    offs, mem, _ = _rand_stream(rng, 32, 8)
+    short = star.UpdateStream(offs, mem)
+    hp = dict(lr=0.1, momentum_coef=0.9, want_norms=True)
+    c = star.star_plan_choice(50_000_000, 32, "f32", short, **hp)
+    assert (c["kernel"], c["collapsed_update"], c["launches"], c["finishing_launches"], c["queue_order"]) == \
+        (star.KERNEL_SEQ, 1, 1, 1, 1)
+    assert c["fma_seq"] - 3 * 8 <= 320
+    assert star.star_plan_choice(50_000_000, 32, "bf16", short, **hp)["kernel"] == star.KERNEL_AFFINE_MFMA
+    assert star.star_plan_choice(50_000_000, 32, "f32", short, kernel=star.KERNEL_AFFINE_MFMA, **hp)["kernel"] == \
+        star.KERNEL_AFFINE_MFMA
+    c = star.star_plan_choice(50_000_000, 32, "f32", short, kernel=star.KERNEL_SEQ, **hp)
+    assert c["kernel"] == star.KERNEL_SEQ and c["collapsed_update"] == 0
+    assert star.star_plan_choice(50_000_000, 32, "f32", short, update=False, want_norms=True)["kernel"] == \
+        star.KERNEL_AFFINE_MFMA
+    offs, mem, _ = _rand_stream(rng, 32, 64)
+    c = star.star_plan_choice(50_000_000, 32, "f32", star.UpdateStream(offs, mem), **hp)
+    assert c["kernel"] == star.KERNEL_AFFINE_MFMA and c["collapsed_update"] == 1
+    offs, mem, _ = _rand_stream(rng, 16, 8)
+    assert star.star_plan_choice(50_000_000, 16, "f32", star.UpdateStream(offs, mem), **hp)["kernel"] == \
+        star.KERNEL_AFFINE_MFMA
+
+
 def test_plan_choice_reports_the_kernels_of_the_five_workloads():
     """What bench.py labels its roofline with: the library's own answer, for every workload as it is timed."""
     import workloads
