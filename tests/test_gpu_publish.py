@@ -13,10 +13,11 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("pub", ["f32", "bf16"])
-@pytest.mark.parametrize("kern", [star.KERNEL_SEQ, star.KERNEL_AFFINE])
+@pytest.mark.parametrize("kern", [star.KERNEL_SEQ, star.KERNEL_AFFINE, None])
 @pytest.mark.parametrize("W,P,U,dtype,norms,shift", [
     (4, 5, 3, "f32", False, 0), (8, 70001, 12, "f32", True, 0), (16, 123457, 20, "bf16", True, 0),
     (32, 40003, 6, "bf16", True, 0), (3, 9001, 300, "f32", True, 0), (5, 30011, 7, "f32", False, 1),
+    (24, 30011, 5, "f32", True, 0),      # the library's own choice here: collapsed update with direct norm sums
 ])
 def test_publish(pub, kern, W, P, U, dtype, norms, shift):
     rng = np.random.default_rng(17 * W + U)
