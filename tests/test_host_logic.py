@@ -90,7 +90,7 @@ def test_options_are_checked_before_anything_else():
     assert lib.star_plan_choice(8, 4, 0, ctypes.byref(us.c), ctypes.byref(hp), 1, 0, ctypes.byref(o), ctypes.byref(info)) == 6
 
 
-@pytest.mark.parametrize("claim", [1, 3, 5])
+@pytest.mark.parametrize("claim", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 255, 256, 257, 512, 608, 1024])
 def test_first_round_of_claims_tiles_the_front_of_the_shard(G, claim):
     """The fixed first claims are disjoint, leave no gap, start at tile 0 and end where the counter
