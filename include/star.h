@@ -100,13 +100,16 @@ typedef enum {
 /* How the U updates are evaluated on the device (both give the same result up
  * to fp32 rounding; see star_plan_affine). */
 typedef enum {
-    STAR_KERNEL_AUTO = 0,  /* a single update on fp32 rows: SEQ; otherwise AFFINE_MFMA        */
-    STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers                    */
+    STAR_KERNEL_AUTO = 0,  /* the library chooses (star_plan_choice tells what): a single update on fp32
+                              rows SEQ, otherwise the collapsed map; with norms the Gram matrix on the
+                              matrix cores (up to 6 rows: vector registers), except that coefficients of
+                              both signs and short streams on 17 to 32 fp32 rows get direct norm sums     */
+    STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers; norms from direct sums of
+                              gbar_u^2                                                                   */
     STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
                                matrix behind the norms in vector registers up to 16 rows             */
     STAR_KERNEL_AFFINE_MFMA = 3 /* the same map, the Gram matrix formed on the matrix cores for any number
-                                   of rows (what AUTO uses with the collapsed evaluation, except for
-                                   up to 6 rows, where it keeps the vector registers)                 */
+                                   of rows                                                            */
 } star_kernel;
 
 /*
