@@ -162,12 +162,13 @@ typedef struct {
  * Precision of the norms.  For a stream of two or more updates they are derived
  * from the Gram matrix of the rows, n_u^2 = c_u^T Gamma c_u (one pass whatever
  * U is).  That form is as accurate as its terms are free of cancellation: the
- * relative error of n_u is at most 1e-7 * kappa_u,
+ * relative error of n_u is at most 2e-8 * kappa_u,
  *     kappa_u = (sum_w |c_{u,w}| ||g_w||)^2 / n_u^2,
- * which lies between 1 and y_u for non-negative weights on rows that are not
- * anti-correlated (every weighting of the paper; observed errors are 1e-7 and
- * less there) and grows without bound when a group's weighted sum nearly
- * cancels.  With coefficients of both signs (STAR_W_EXPLICIT) the library
+ * which lies between 1 and y_u <= 32 for non-negative weights on rows that are
+ * not anti-correlated (every weighting of the paper: at most 6.4e-7, observed
+ * 1e-7 and less) and grows without bound when a group's weighted sum nearly
+ * cancels (measured at kappa = 4e4: 2.6e-6 with the vector-register Gram
+ * matrix, 1.8e-5 with the matrix-core one).  With coefficients of both signs (STAR_W_EXPLICIT) the library
  * therefore takes the norms from direct sums of gbar_u^2 in a pass of its
  * own (error 1e-6 or less, one more read of the rows); star_options.kernel =
  * STAR_KERNEL_SEQ forces that direct form for any stream.

@@ -139,7 +139,7 @@ def test_signed_coefficients_take_the_direct_norm_route():
 def test_anticorrelated_rows_hold_the_documented_norm_bound(kname):
     """g_1 = -g_0 + small noise under plain mean weights: the group average nearly cancels although every
     coefficient is positive.  The header's bound for norms that come from the Gram matrix: relative error
-    at most 1e-7 * kappa_u (kappa_u as computed above; 1..y_u for ordinary groups).  The direct route
+    at most 2e-8 * kappa_u (kappa_u as computed above; 1..y_u for ordinary groups).  The direct route
     (seq) is not subject to it and holds 1e-6."""
     rng = np.random.default_rng(44)
     W, P = 4, 200003
@@ -160,8 +160,7 @@ def test_anticorrelated_rows_hold_the_documented_norm_bound(kname):
     if kname == "seq":
         assert err.max() <= 1e-6
     else:
-        assert np.all(err <= 1e-7 * kappa)
-        assert err[1] <= 1e-6 and err[2] <= 1e-6 * max(1.0, kappa[2] / 4)
+        assert np.all(err <= 2e-8 * kappa)
 
 
 def test_two_threads_with_different_options():
