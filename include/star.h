@@ -190,7 +190,10 @@ star_status star_group_update(float *params, float *momentum, const void *const 
  * STAR_NOALLOC_SCRATCH_BYTES that is part of the library's device code (every
  * GPU the library runs on holds one copy until the process ends), and carries
  * the group tables to it in kernel arguments.  It calls no hipMalloc, hipFree,
- * hipHostMalloc, event or copy routine.
+ * hipHostMalloc, event or copy routine, and enqueues kernels only (no memset,
+ * no copy), so a call can be captured into a HIP graph and replayed; make one
+ * ordinary call on the device first (the array's address is resolved on first
+ * use).
  *   - at most STAR_NOALLOC_MAX_UPDATES updates per call; a longer stream is
  *     rejected with STAR_ERR_SHAPE before anything is enqueued (split it over
  *     several calls, the state carries over).

@@ -146,3 +146,44 @@ def test_noalloc_through_ctypes_directly():
     assert rc == 0, star.last_error()
     torch.cuda.synchronize()
     assert torch.equal(p, p_ref) and torch.equal(v, v_ref) and torch.equal(n, n_ref)
+
+
+def test_noalloc_under_graph_capture():
+    """What the entry point is for: captured into a HIP graph (no allocation, no memset, no copy: kernels only)
+    and replayed, with eager work and synchronisations between the replays; every replay must leave what the same
+    number of eager calls leaves."""
+    rng = np.random.default_rng(5)
+    W, P, U = 16, 300007, 12
+    rows = [torch.from_numpy((rng.standard_normal(P) * 1e-2).astype(np.float32)).cuda() for _ in range(W)]
+    offs, mem = [0], []
+    for _ in range(U):
+        y = int(rng.integers(1, W + 1))
+        mem += [int(x) for x in rng.permutation(W)[:y]]
+        offs.append(len(mem))
+    us = star.UpdateStream(offs, mem)
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3)
+    p0 = torch.from_numpy((rng.standard_normal(P) * 0.02).astype(np.float32)).cuda()
+    # eager reference: the state after 1, 2, 3 calls (this also resolves the array's address outside the capture)
+    p, v, n = p0.clone(), torch.zeros(P, device="cuda"), torch.zeros(U, device="cuda")
+    ref = []
+    for _ in range(3):
+        star.star_group_update_noalloc(p, v, rows, us, norms_out=n, **hp)
+        torch.cuda.synchronize()
+        ref.append((p.clone(), v.clone(), n.clone()))
+    # capture one call, replay three times from the same start
+    p.copy_(p0)
+    v.zero_()
+    n.zero_()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        star.star_group_update_noalloc(p, v, rows, us, norms_out=n, **hp)
+    torch.cuda.synchronize()
+    assert torch.equal(p, p0)                     # capturing runs nothing
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for k in range(3):
+        g.replay()
+        scratch.add_(1.0)                         # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(p, ref[k][0]) and torch.equal(v, ref[k][1]), f"replay {k}"
+        assert torch.allclose(n, ref[k][2], rtol=1e-6, atol=0.0), f"replay {k}"
