@@ -153,6 +153,41 @@ def test_full_size_workload(name):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("norms", [True, False])
+def test_long_shard_of_wide_fp32_rows(norms):
+    """24 fp32 rows on a shard long enough for queue order (20 M elements), a shape none of the five workloads has:
+    with norms the collapsed update with direct norm sums, without them the plain collapsed kernel with claims of
+    two tiles.  State on one element of every block of 512, every norm against the oracle over the whole shard."""
+    wl = workloads.WORKLOADS["bert_base"].scaled(20_000_003)
+    import dataclasses
+    wl = dataclasses.replace(wl, W=24, U=8, heavy_frac=0.0, norms=norms)
+    rng = np.random.default_rng(9)
+    idx = sample_indices(wl.P, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    p = workloads.make_params(wl, 0, "cuda")
+    v = workloads.make_momentum(wl, "cuda")
+    rows = workloads.make_grad_rows(wl, 0, 0, "cuda")
+    s = workloads.make_update_stream(wl, 0, 0)
+    us = star.UpdateStream(s["offsets"], s["members"], s["staleness"])
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    c = star.star_plan_choice(wl.P, wl.W, "f32", us, want_norms=norms, **hp)
+    assert c["queue_order"] == 1 and c["collapsed_update"] == 1
+    assert c["kernel"] == (star.KERNEL_SEQ if norms else star.KERNEL_AFFINE)
+    ep, ev = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
+    n = torch.zeros(wl.U, device="cuda") if norms else None
+    star.star_group_update(p, v, rows, us, norms_out=n, **hp)
+    torch.cuda.synchronize()
+    ep, ev, _ = so.group_update(ep, ev, rows_at(rows, idx_dev), s["offsets"], s["members"], staleness=s["staleness"], **hp)
+    e_p, e_v = so.max_rel_err(p[idx_dev].cpu().numpy(), ep), so.max_rel_err(v[idx_dev].cpu().numpy(), ev)
+    print(f"wide fp32 rows, norms={norms}: {idx.size} elements, err params {e_p:.3g} momentum {e_v:.3g}", flush=True)
+    assert e_p <= 1e-6 and e_v <= 1e-6
+    if norms:
+        en = oracle_norms([to_host(r) for r in rows], s, wl.wmode, np.arange(wl.U))
+        e_n = float(np.max(np.abs(n.cpu().numpy() - en) / en))
+        print(f"  all {wl.U} norms vs the oracle over the whole shard: {e_n:.3g}", flush=True)
+        assert e_n <= 1e-6
+
+
 @pytest.mark.parametrize("name", ["bert_base", "vgg16"])
 def test_full_size_publish_and_reduce(name):
     """The widened entry points at full workload size, on one element of every block of 512: update with a
