@@ -43,8 +43,16 @@ __device__ __forceinline__ void gram_step(float (&acc)[W * (W + 1) / 2], const f
 // KCH: chunks a thread loads together per tile when the tiles come from the queue (a tile is then
 // KCH * 256 chunks).  More than one only for the Gram matrix alone on very few rows: a thread that loads 8
 // to 32 bytes per tile keeps too little in flight (1 fp32 row: 0.40 of the HBM peak), whatever the claim.
-template <int W, class R, bool UPDATE, bool GRAM, int KCH = 1>
-__global__ __launch_bounds__(kBlock) void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
+// ONE_WAVE: the launch runs one wave per SIMD (the half-size workgroups of the update on 24 and more bf16 rows:
+// two of 128 threads per compute unit).  Telling the compiler so lets it spend registers on issuing a tile's 34
+// loads together instead of saving them for an occupancy the launch never uses: 32 bf16 rows, 138 M elements,
+// 1.84 against 1.89-1.91 ms.  The limit is enforced by the hardware too, so only launches that take their tiles
+// from the queue use these instantiations (a short shard with one tile per workgroup needs many workgroups per
+// unit: 0.52 against 0.71 of the HBM peak on 12 M elements), and 8 or 16 rows, which run one wave per SIMD as
+// well, measured 1-2 % slower with it.
+template <int W, class R, bool UPDATE, bool GRAM, int KCH = 1, bool ONE_WAVE = false>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, ONE_WAVE ? 1 : 8)))
+void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const RowPtrs rows, const AffCoef cf, const int64_t P,
                                                      const int vec_ok, const int span_g, const int span_k,
                                                      void* __restrict__ publish, const int publish_bf16,
@@ -548,10 +556,17 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     // and fp32 rows do not care.  With these half-size tiles claims of 4 (4 KB of every row, 8 KB of the
     // state) are the fastest: 1-4 % ahead of 3 on every box and shard length tried (32 rows, 138 M
     // elements: 1.81 against 1.89 ms; 24 rows 1.43 against 1.53 ms), 5 to 12 fall off again.
-    if (queued && std::is_same<R, RowBf16x4>::value && W >= 24) {
-        g.threads = kBlock / 2;
-        g.grid = g.span_g = std::min(2 * g.grid, grid_cap);
-        g.claim = 4;
+    if constexpr (std::is_same<R, RowBf16x4>::value && W >= 24 && UPDATE && !GRAM) {
+        if (queued) {
+            g.threads = kBlock / 2;
+            g.grid = g.span_g = std::min(2 * g.grid, grid_cap);
+            g.claim = 4;
+            *grid_out = g.grid;
+            hipLaunchKernelGGL((aff_kernel<W, R, UPDATE, GRAM, 1, true>), dim3(g.grid), dim3(g.threads), 0, s, a.params,
+                               a.momentum, a.rows, a.cf, a.P, a.vec_ok, g.span_g, g.span_k, a.publish,
+                               a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue, g.claim);
+            return hipGetLastError();
+        }
     }
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(g.threads), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
