@@ -17,8 +17,8 @@ many launches it timed and how many followed them (the first-call samples), and 
 main kernel in the trace are counted back from the end.  The wake-up and warm-up launches, which run up
 to 15 % slower, are left out, so the kernel's average can be held against bench.py's own step time.
 
-    python -m paper_2512_09685_amd.rocprof_summary --workload bert_base --dir gpurun_out/prof/bert_base
-    python -m paper_2512_09685_amd.rocprof_summary --all-workloads-dir gpurun_out/prof/all [--op reduce]
+    python -m paper_2512_09685_amd.rocprof_summary --workload bert_base --dir out/prof/bert_base
+    python -m paper_2512_09685_amd.rocprof_summary --all-workloads-dir out/prof/all [--op reduce]
 """
 from __future__ import annotations
 
