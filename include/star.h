@@ -129,8 +129,9 @@ typedef struct {
     int64_t queue_threshold; /* shards of at least this many elements are processed by long-lived
                                 workgroups that claim tiles (1024 consecutive elements of every
                                 buffer) in address order from a work queue; shorter ones get a fixed
-                                assignment, which starts faster.  0 = default (16 Mi elements);
-                                1 = always the queue; negative: STAR_ERR_SHAPE                         */
+                                assignment, which starts faster.  0 = default (updates: 16 Mi elements
+                                with fp32 rows, 32 Mi with up to 4 of them, 48 Mi with bf16 rows; other
+                                launches 16 Mi); 1 = always the queue; negative: STAR_ERR_SHAPE         */
 } star_options;
 
 /* The stream of updates of one call (all arrays on the host).  Group u is

@@ -48,12 +48,25 @@ const int g_env_kernel = initial_kernel_choice();   // what STAR_KERNEL_AUTO mea
 // The options of one call, resolved: never a process-wide state.
 struct Opts {
     int kernel = STAR_KERNEL_AUTO;
-    int64_t queue_min = star::kQueueMinElements;
+    int64_t queue_min = 0;   // 0: the library's default for the call's shape (queue_min_for)
 };
+
+// Shards of at least this many elements take their tiles from the queue.  The queue's order pays once a call is
+// long enough for its start-up (the first claims) and its few claims per workgroup not to show: measured on
+// 2-96 Mi elements, 16 updates, that is from about 16 Mi elements on with 8 and more fp32 rows (16 Mi: 0.76
+// against 0.66 of the HBM peak with 8 rows, equal with 16), from about 32 Mi with up to 4 fp32 rows, and from
+// about 48 Mi with bf16 rows, whose tiles are half as heavy (16-32 Mi: the fixed assignment is 0-14 % ahead,
+// 64 Mi and more: the queue 2-8 %).  The launches without update keep 16 Mi.
+int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update) {
+    if (opt.queue_min > 0) return opt.queue_min;
+    if (!update) return star::kQueueMinElements;
+    if (grad_dtype == STAR_BF16) return 3 * star::kQueueMinElements;
+    return rows <= 4 ? 2 * star::kQueueMinElements : star::kQueueMinElements;
+}
 
 star_status resolve_options(const star_options* o, Opts* out) {
     out->kernel = g_env_kernel;
-    out->queue_min = star::kQueueMinElements;
+    out->queue_min = 0;
     if (!o) return STAR_OK;
     if (o->kernel != STAR_KERNEL_AUTO && o->kernel != STAR_KERNEL_SEQ && o->kernel != STAR_KERNEL_AFFINE &&
         o->kernel != STAR_KERNEL_AFFINE_MFMA)
@@ -263,7 +276,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
         else l.route = star::Route::Seq;
     }
     l.Wp = star::padded_rows(plan.Wc);
-    l.want_queue = P >= opt.queue_min;
+    l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update);
     // 17 to 32 fp32 rows, update with norms: the Gram matrix needs the fp32 matrix instructions (1536 flops per
     // element, only partly hidden: 0.60-0.64 of the HBM peak).  A short stream gets its norms cheaper from the
     // direct sums, y_u + 1 multiply-adds per update, in the same pass as the collapsed update.
@@ -616,7 +629,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         a.vec_ok = vec_ok ? 1 : 0;
         a.norms = want_norms ? 1 : 0;
         a.partials = slot->partials;
-        a.queue = P >= opt.queue_min ? slot->queue : nullptr;
+        a.queue = P >= queue_min_for(opt, grad_dtype, Wc, false) ? slot->queue : nullptr;
         int grid = 0;
         hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
         if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
@@ -666,7 +679,7 @@ star_status run_gram(const void* const* grad_rows, int grad_dtype, int64_t P, in
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
     const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel, false);
-    a.queue = (mfma || P >= opt.queue_min) ? slot->queue : nullptr;
+    a.queue = (mfma || P >= queue_min_for(opt, grad_dtype, W, false)) ? slot->queue : nullptr;
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
     if (e != hipSuccess) return hip_fail(e, "launch of the Gram kernel");

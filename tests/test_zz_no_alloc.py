@@ -56,7 +56,7 @@ CASES = [
     ((32, 150001, 40, "bf16", True), (17, 33333, 9, "bf16", True)),      # wide tiles, bf16 rows
     ((8, 400003, 1, "f32", True), (8, 9001, 1, "f32", True)),            # a single update: step-by-step kernel
     ((12, 250001, 16, "bf16", False), (5, 1025, 3, "bf16", False)),      # no norms: nothing but the update
-    ((8, 17 * 1024 * 1024 + 5, 6, "bf16", True), (8, 16 * 1024 * 1024 + 1027, 6, "bf16", False)),   # tiles from the queue
+    ((8, 17 * 1024 * 1024 + 5, 6, "f32", True), (8, 16 * 1024 * 1024 + 1027, 6, "f32", False)),     # tiles from the queue
     ((32, 150001, 20, "f32", True), (20, 33333, 8, "f32", True)),        # wide fp32 rows: collapsed update, direct norms
 ]
 
