@@ -240,11 +240,15 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
 // tile of few bf16 rows is so light that the vector-register form's per-chunk work shows: there the matrix
 // cores are ahead from 4 rows on (134 M elements, 4 / 5 / 6 bf16 rows: 0.57 / 0.65 / 0.71 of the HBM peak
 // against 0.48 / 0.55 / 0.43; fp32 rows: 0.46 / 0.56 / 0.65 against 0.80 / 0.82 / 0.65).
-bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update) {
+// On shards below 16 Mi elements an update with norms on 7 or 8 rows is faster with the vector-register form and
+// its fixed assignment as well (36 accumulators still leave room): 1 Mi elements 21 against 28 us, 8 Mi 80
+// against 89 us, equal at 16 Mi; 16 rows are faster on the matrix cores at every length.
+bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update, int64_t P) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
     if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
     if (!update && grad_dtype == STAR_BF16) return Wp >= 4;
+    if (update && Wp <= 8 && P < star::kQueueMinElements) return false;
     return Wp > star::kFewRows;
 }
 
@@ -288,7 +292,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     }
     if (l.route == star::Route::Affine) {
         const bool gram = want_norms;
-        l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update);
+        l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update, P);
         l.queue_order = l.mfma || (l.want_queue && star::aff_takes_queue(gram, l.Wp));
         l.launches = (update || gram) ? 1 : 0;
         l.finishing = gram ? 2 : 0;
@@ -678,7 +682,7 @@ star_status run_gram(const void* const* grad_rows, int grad_dtype, int64_t P, in
     a.partials = slot->partials;
     int grid = 0;
     const int Wp = star::padded_rows(W);   // rows beyond W repeat the last one; their entries are not copied out
-    const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel, false);
+    const bool mfma = gram_on_matrix_cores(Wp, grad_dtype, opt.kernel, false, P);
     a.queue = (mfma || P >= queue_min_for(opt, grad_dtype, W, false)) ? slot->queue : nullptr;
     hipError_t e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, false, a, num_cu, star::kGridCap, &grid, stream)
                         : star::launch_affine(Wp, grad_dtype, false, true, a, num_cu, star::kGridCap, &grid, stream);
