@@ -358,3 +358,21 @@ def test_header_is_plain_c_and_links(tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.split()[0] == str(len(names)), (r.returncode, r.stdout, r.stderr)
+
+
+def test_host_planner_and_selector_under_sanitizers(tmp_path):
+    """The pure-host sources (planner, mode selector) built with the address and undefined-behaviour
+    sanitizers take random update streams, valid and broken, and random iteration times: every call
+    returns a status and neither sanitizer reports anything (a report ends the program with an error)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2512_09685_amd", "csrc")
+    exe = tmp_path / "host_fuzz"
+    r = subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                        "-I", os.path.join(root, "include"), "-I", csrc, os.path.join(root, "tests", "host_fuzz.cpp"),
+                        os.path.join(csrc, "star_plan.cpp"), os.path.join(csrc, "star_select.cpp"), "-o", str(exe)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe), "20000", "10000"], capture_output=True, text=True)
+    assert r.returncode == 0, (r.stdout, r.stderr[-2000:])
+    assert "plans accepted" in r.stdout and "selector calls accepted 20000" in r.stdout
