@@ -112,6 +112,14 @@ typedef enum {
                                    of rows                                                            */
 } star_kernel;
 
+/* star_options.flags.  STAR_OPT_DIRECT_NORMS: where the library would take the norms from the Gram
+ * matrix of the rows (relative error up to 2e-8 kappa_u, see star_group_update), take them from direct
+ * sums of gbar_u^2 instead, to fp32-product accuracy whatever the rows: in a pass of its own over the
+ * rows beside the collapsed update (W more row reads per element), as the library does by itself for
+ * coefficients of both signs.  For rows that may be anti-correlated.  Ignored when `kernel` forces an
+ * evaluation (STAR_KERNEL_SEQ always sums directly) and by calls that return no norms. */
+#define STAR_OPT_DIRECT_NORMS 1
+
 /*
  * Per-call options of the *_opt entry points (host struct, read before the
  * call returns).  All zero = the defaults; a NULL pointer means the same.
@@ -125,7 +133,7 @@ typedef enum {
  */
 typedef struct {
     int32_t kernel;          /* star_kernel; STAR_KERNEL_AUTO = the library chooses                    */
-    int32_t reserved;        /* must be 0                                                              */
+    int32_t flags;           /* 0 or STAR_OPT_DIRECT_NORMS; any other bit: STAR_ERR_SHAPE              */
     int64_t queue_threshold; /* shards of at least this many elements are processed by long-lived
                                 workgroups that claim tiles (1024 consecutive elements of every
                                 buffer) in address order from a work queue; shorter ones get a fixed
@@ -171,8 +179,10 @@ typedef struct {
  * cancels (measured at kappa = 4e4: 2.6e-6 with the vector-register Gram
  * matrix, 1.8e-5 with the matrix-core one).  With coefficients of both signs (STAR_W_EXPLICIT) the library
  * therefore takes the norms from direct sums of gbar_u^2 in a pass of its
- * own (error 1e-6 or less, one more read of the rows); star_options.kernel =
- * STAR_KERNEL_SEQ forces that direct form for any stream.
+ * own (error 1e-6 or less, one more read of the rows); star_options.flags =
+ * STAR_OPT_DIRECT_NORMS asks for the same on any stream (the update stays the
+ * collapsed one), and star_options.kernel = STAR_KERNEL_SEQ evaluates update
+ * and norms step by step.
  * Non-finite gradient values propagate: params and momentum of an element turn
  * non-finite when a member of any group holds inf or NaN there (inf may come
  * out as NaN), and norms_out[u] is non-finite exactly for the groups with such

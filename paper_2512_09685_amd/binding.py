@@ -40,7 +40,7 @@ class _HParams(ctypes.Structure):
 
 
 class _Options(ctypes.Structure):
-    _fields_ = [("kernel", ctypes.c_int32), ("reserved", ctypes.c_int32), ("queue_threshold", ctypes.c_int64)]
+    _fields_ = [("kernel", ctypes.c_int32), ("flags", ctypes.c_int32), ("queue_threshold", ctypes.c_int64)]
 
 
 class _PlanInfo(ctypes.Structure):
@@ -51,12 +51,15 @@ class _PlanInfo(ctypes.Structure):
                 ("fma_seq", ctypes.c_double), ("fma_affine", ctypes.c_double)]
 
 
-def _options(kernel, queue_threshold):
-    """star_options for a call, or None when the caller left both at their defaults (the plain entry
-    point is called then)."""
-    if kernel is None and queue_threshold is None:
+OPT_DIRECT_NORMS = 1
+
+
+def _options(kernel, queue_threshold, direct_norms=False):
+    """star_options for a call, or None when the caller left everything at its default (the plain
+    entry point is called then)."""
+    if kernel is None and queue_threshold is None and not direct_norms:
         return None
-    return _Options(int(kernel or 0), 0, int(queue_threshold or 0))
+    return _Options(int(kernel or 0), OPT_DIRECT_NORMS if direct_norms else 0, int(queue_threshold or 0))
 
 
 _lib = None
@@ -179,13 +182,13 @@ def _stream_handle(stream):
 
 def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStream, *, lr: float, momentum_coef: float,
                       weight_decay: float = 0.0, wmode="mean", scale_lr_by_group: bool = False, norms_out=None,
-                      stream=None, kernel=None, queue_threshold=None) -> None:
+                      stream=None, kernel=None, queue_threshold=None, direct_norms: bool = False) -> None:
     """U group updates of one shard, in place, enqueued on ``stream``
     (default: torch's current stream).  ``params``/``momentum``: float32 CUDA
     tensors [P]; ``grad_rows``: W tensors [P] (float32 or bfloat16);
     ``norms_out``: float32 CUDA tensor [U] or None.  ``kernel`` /
-    ``queue_threshold``: the fields of ``star_options`` (the call then goes
-    through ``star_group_update_opt``)."""
+    ``queue_threshold`` / ``direct_norms``: the fields of ``star_options`` (the
+    call then goes through ``star_group_update_opt``)."""
     lib = load_library()
     P = int(params.shape[0])
     if not (params.is_contiguous() and momentum.is_contiguous()) or momentum.shape[0] != P:
@@ -194,7 +197,7 @@ def star_group_update(params, momentum, grad_rows: Sequence, updates: UpdateStre
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
     if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
         raise ValueError("norms_out must hold U floats")
-    opt = _options(kernel, queue_threshold)
+    opt = _options(kernel, queue_threshold, direct_norms)
     n_ptr = None if norms_out is None else norms_out.data_ptr()
     if opt is None:
         _check(lib.star_group_update(params.data_ptr(), momentum.data_ptr(), ptrs, dt, P, len(grad_rows),
@@ -226,7 +229,7 @@ def star_group_update_noalloc(params, momentum, grad_rows: Sequence, updates: Up
 def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: UpdateStream, publish, *, lr: float,
                               momentum_coef: float, weight_decay: float = 0.0, wmode="mean",
                               scale_lr_by_group: bool = False, norms_out=None, stream=None, kernel=None,
-                              queue_threshold=None) -> None:
+                              queue_threshold=None, direct_norms: bool = False) -> None:
     """star_group_update that also writes the updated parameters into ``publish``
     (float32 or bfloat16 CUDA tensor [P]) in the same pass."""
     import torch
@@ -240,7 +243,7 @@ def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: Up
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
     if norms_out is not None and (norms_out.shape[0] < updates.U or not norms_out.is_contiguous()):
         raise ValueError("norms_out must hold U floats")
-    opt = _options(kernel, queue_threshold)
+    opt = _options(kernel, queue_threshold, direct_norms)
     n_ptr = None if norms_out is None else norms_out.data_ptr()
     pdt = F32 if publish.dtype == torch.float32 else BF16
     if opt is None:
@@ -254,13 +257,13 @@ def star_group_update_publish(params, momentum, grad_rows: Sequence, updates: Up
 
 
 def star_group_norms(grad_rows: Sequence, updates: UpdateStream, norms_out, *, wmode="mean", stream=None,
-                     kernel=None, queue_threshold=None) -> None:
+                     kernel=None, queue_threshold=None, direct_norms: bool = False) -> None:
     lib = load_library()
     P = int(next(r for r in grad_rows if r is not None).shape[0])
     ptrs, dt = _rows(grad_rows, P)
     if norms_out.shape[0] < updates.U or not norms_out.is_contiguous():
         raise ValueError("norms_out must hold U floats")
-    opt = _options(kernel, queue_threshold)
+    opt = _options(kernel, queue_threshold, direct_norms)
     wm = _WMODES[wmode] if isinstance(wmode, str) else wmode
     if opt is None:
         _check(lib.star_group_norms(ptrs, dt, P, len(grad_rows), ctypes.byref(updates.c), wm, norms_out.data_ptr(),
@@ -307,14 +310,14 @@ def star_plan_affine(W: int, updates: UpdateStream, *, lr: float, momentum_coef:
 
 def star_plan_choice(P: int, W: int, grad_dtype, updates: UpdateStream, *, lr: float = 0.0, momentum_coef: float = 0.0,
                      weight_decay: float = 0.0, wmode="mean", scale_lr_by_group: bool = False, update: bool = True,
-                     want_norms: bool = False, kernel=None, queue_threshold=None) -> dict:
+                     want_norms: bool = False, kernel=None, queue_threshold=None, direct_norms: bool = False) -> dict:
     """Host-only: what the library would launch for this call (the fields of
     ``star_plan_info``).  ``grad_dtype``: "f32" | "bf16" or the dtype code."""
     lib = load_library()
     hp = _hparams(lr, momentum_coef, weight_decay, wmode, scale_lr_by_group)
     dt = {"f32": F32, "bf16": BF16}.get(grad_dtype, grad_dtype)
     info = _PlanInfo()
-    opt = _options(kernel, queue_threshold)
+    opt = _options(kernel, queue_threshold, direct_norms)
     _check(lib.star_plan_choice(P, W, dt, ctypes.byref(updates.c), ctypes.byref(hp), int(bool(update)),
                                 int(bool(want_norms)), None if opt is None else ctypes.byref(opt), ctypes.byref(info)))
     return {name: getattr(info, name) for name, _ in _PlanInfo._fields_}

@@ -49,6 +49,7 @@ const int g_env_kernel = initial_kernel_choice();   // what STAR_KERNEL_AUTO mea
 struct Opts {
     int kernel = STAR_KERNEL_AUTO;
     int64_t queue_min = 0;   // 0: the library's default for the call's shape (queue_min_for)
+    bool direct_norms = false;   // STAR_OPT_DIRECT_NORMS
 };
 
 // Shards of at least this many elements take their tiles from the queue.  The queue's order pays once a call is
@@ -67,11 +68,13 @@ int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update) {
 star_status resolve_options(const star_options* o, Opts* out) {
     out->kernel = g_env_kernel;
     out->queue_min = 0;
+    out->direct_norms = false;
     if (!o) return STAR_OK;
     if (o->kernel != STAR_KERNEL_AUTO && o->kernel != STAR_KERNEL_SEQ && o->kernel != STAR_KERNEL_AFFINE &&
         o->kernel != STAR_KERNEL_AFFINE_MFMA)
         return set_err(STAR_ERR_KERNEL, "unknown kernel choice in star_options");
-    if (o->reserved != 0) return set_err(STAR_ERR_SHAPE, "star_options.reserved must be 0");
+    if (o->flags & ~STAR_OPT_DIRECT_NORMS) return set_err(STAR_ERR_SHAPE, "unknown bit in star_options.flags");
+    out->direct_norms = (o->flags & STAR_OPT_DIRECT_NORMS) != 0;
     if (o->queue_threshold < 0) return set_err(STAR_ERR_SHAPE, "star_options.queue_threshold is negative");
     if (o->kernel != STAR_KERNEL_AUTO) out->kernel = o->kernel;
     if (o->queue_threshold > 0) out->queue_min = o->queue_threshold;
@@ -274,8 +277,10 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     // the weightings of the paper (c >= 0) they cancel only if the rows themselves are anti-correlated;
     // with caller-given coefficients of both signs they cancel as a rule (a difference of two similar
     // rows).  Unless the caller forces an evaluation, such streams get their norms from the direct sums
-    // of gbar^2 (step-by-step kernel, norms only), in a pass of its own beside the collapsed update.
-    if (want_norms && plan.negative_coef && opt.kernel == STAR_KERNEL_AUTO && l.route == star::Route::Affine) {
+    // of gbar^2 (step-by-step kernel, norms only), in a pass of its own beside the collapsed update; so
+    // does any stream whose caller asks for it (STAR_OPT_DIRECT_NORMS).
+    if (want_norms && (plan.negative_coef || opt.direct_norms) && opt.kernel == STAR_KERNEL_AUTO &&
+        l.route == star::Route::Affine) {
         if (update) l.split_norms = true;
         else l.route = star::Route::Seq;
     }
@@ -356,7 +361,7 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
     const Launch how = decide(plan, grad_dtype, update, want_norms, P, opt);
     if (how.split_norms) {
         // the rows do not change during the call, so the norms may come first
-        const star_options direct = {STAR_KERNEL_SEQ, 0, opt.queue_min};
+        const star_options direct = {STAR_KERNEL_SEQ, 0, opt.queue_min};   // the step-by-step kernel's sums are direct
         st = run(false, nullptr, nullptr, grad_rows, grad_dtype, P, W, upd, nullptr, hp->wmode, norms_out, nullptr, 0,
                  &direct, hip_stream, no_alloc);
         if (st != STAR_OK) return st;

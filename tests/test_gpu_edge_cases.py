@@ -163,6 +163,52 @@ def test_anticorrelated_rows_hold_the_documented_norm_bound(kname):
         assert np.all(err <= 2e-8 * kappa)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_direct_norms_option_on_anticorrelated_rows(dt):
+    """The same kind of rows with STAR_OPT_DIRECT_NORMS: the update is still the collapsed one, the
+    norms come from direct sums in a pass of their own and hold 1e-6 on the cancelling group too, where
+    the Gram route of the same call without the flag is allowed 2e-8 * kappa."""
+    rng = np.random.default_rng(46)
+    W, P = 8, 300011
+    rows = rand_rows(rng, W, P, dt)
+    as_f = (lambda r: r) if dt == "f32" else (lambda r: (r.astype(np.uint32) << 16).view(np.float32))
+    noise = (rng.standard_normal(P) * 1e-4).astype(np.float32)
+    mirror = -as_f(rows[0]) + noise
+    if dt == "bf16":                      # round to nearest even onto bf16 bit patterns
+        b = mirror.view(np.uint32)
+        mirror = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+    rows[1] = mirror
+    offs = np.array([0, 2, 4, 8, 16], np.int32)
+    mem = np.array([0, 1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 3, 4, 5, 6, 7], np.int32)
+    us = star.UpdateStream(offs, mem)
+    coef = np.concatenate([np.full(2, 0.5), np.full(2, 0.5), np.full(4, 0.25), np.full(8, 0.125)])
+    kappa = condition([as_f(r) for r in rows], offs, mem, coef)
+    assert kappa[0] > 1e3
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+    hp = dict(lr=0.1, momentum_coef=0.9, weight_decay=1e-4)
+    ep, ev, en = so.group_update(p0, v0, rows, offs, mem, want_norms=True, **hp)
+    drows = to_dev_rows(rows)
+    out = {}
+    for direct in (False, True):
+        p, v = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
+        n = torch.full((4,), -1.0, device="cuda")
+        star.star_group_update(p, v, drows, us, norms_out=n, direct_norms=direct, **opts(), **hp)
+        torch.cuda.synchronize()
+        out[direct] = (p.cpu().numpy(), v.cpu().numpy(), np.abs(n.cpu().numpy() - en) / en)
+    print(f"direct norms {dt}: kappa {np.round(kappa, 1).tolist()}, err gram {out[False][2].tolist()}, "
+          f"direct {out[True][2].tolist()}", flush=True)
+    assert np.all(out[False][2] <= 2e-8 * kappa + 1e-6)
+    assert out[True][2].max() <= 1e-6
+    for direct in (False, True):
+        assert so.max_rel_err(out[direct][0], ep) <= 1e-6 and so.max_rel_err(out[direct][1], ev) <= 1e-6
+    # norms alone
+    n = torch.zeros(4, device="cuda")
+    star.star_group_norms(drows, us, n, direct_norms=True, **opts())
+    torch.cuda.synchronize()
+    assert np.max(np.abs(n.cpu().numpy() - en) / en) <= 1e-6
+
+
 def test_two_threads_with_different_options():
     """Two host threads call the library at the same time with different per-call options (one forces
     the step-by-step kernel and the queue, the other the collapsed kernel and the fixed assignment);

@@ -65,20 +65,22 @@ def test_empty_stream_and_empty_shard_are_no_ops():
 
 
 def test_options_are_checked_before_anything_else():
-    """star_options of the *_opt entry points: unknown kernel, non-zero reserved field and a negative
+    """star_options of the *_opt entry points: unknown kernel, unknown flag bits and a negative
     threshold are rejected (with fake device addresses: nothing may be touched)."""
     lib = star.load_library()
     us = star.UpdateStream((0, 2), (0, 1))
     hp = binding._HParams(0.1, 0.9, 0.0, 0, 0)
     ptrs = (ctypes.c_void_p * 32)(*([0x3000 + 0x100 * i for i in range(32)]))
 
-    def call(kernel=0, reserved=0, threshold=0, P=8):
-        o = binding._Options(kernel, reserved, threshold)
+    def call(kernel=0, flags=0, threshold=0, P=8):
+        o = binding._Options(kernel, flags, threshold)
         return lib.star_group_update_opt(0x1000, 0x2000, ptrs, 0, P, 4, ctypes.byref(us.c), ctypes.byref(hp), None,
                                          None, 0, ctypes.byref(o), None)
     assert call(kernel=5) == 6 and "kernel" in star.last_error()
     assert call(kernel=-1) == 6
-    assert call(reserved=1) == 2
+    assert call(flags=2) == 2 and "flags" in star.last_error()
+    assert call(flags=-1) == 2
+    assert call(flags=star.OPT_DIRECT_NORMS, P=0) == 0
     assert call(threshold=-1) == 2
     assert call(kernel=3, threshold=1, P=0) == 0            # valid options, empty shard: a no-op
     o = binding._Options(7, 0, 0)
@@ -201,6 +203,28 @@ def test_plan_choice_wide_fp32_rows_with_norms():
     offs, mem, _ = _rand_stream(rng, 16, 8)
     assert star.star_plan_choice(50_000_000, 16, "f32", star.UpdateStream(offs, mem), **hp)["kernel"] == \
         star.KERNEL_AFFINE_MFMA
+
+
+def test_plan_choice_direct_norms_option():
+    """STAR_OPT_DIRECT_NORMS: the update stays collapsed and gets a direct norm pass beside it (one more
+    launch over the rows and its finishing launch instead of the Gram matrix's two); norms alone go to the
+    step-by-step kernel; a forced kernel and a call without norms ignore the flag."""
+    us = star.UpdateStream(np.arange(0, 17, 2, dtype=np.int32), np.tile(np.arange(8, dtype=np.int32), 2))   # 8 groups of 2
+    hp = dict(lr=0.1, momentum_coef=0.9)
+    for dt in ("f32", "bf16"):
+        gram = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, **hp)
+        direct = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, direct_norms=True, **hp)
+        assert gram["kernel"] in (star.KERNEL_AFFINE, star.KERNEL_AFFINE_MFMA) and gram["launches"] == 1
+        assert gram["finishing_launches"] == 2
+        assert direct["kernel"] == star.KERNEL_AFFINE and direct["collapsed_update"] == 1
+        assert direct["launches"] == 2 and direct["finishing_launches"] == 1
+        alone = star.star_plan_choice(1 << 20, 8, dt, us, update=False, want_norms=True, direct_norms=True, **hp)
+        assert alone["kernel"] == star.KERNEL_SEQ
+        forced = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, direct_norms=True,
+                                       kernel=star.KERNEL_AFFINE_MFMA, **hp)
+        assert forced["kernel"] == star.KERNEL_AFFINE_MFMA and forced["launches"] == 1
+        plain = star.star_plan_choice(1 << 20, 8, dt, us, direct_norms=True, **hp)
+        assert plain == star.star_plan_choice(1 << 20, 8, dt, us, **hp)
 
 
 def test_plan_choice_reports_the_kernels_of_the_five_workloads():
