@@ -290,7 +290,8 @@ typedef struct {
                                    (the collapsed map without norms needs no tables at all and reports 1)   */
     int32_t collapsed_update;   /* 1: params and momentum come from the one affine map of the stream.  Always so
                                    with AFFINE and AFFINE_MFMA; with SEQ only for 17 to 32 fp32 rows, update
-                                   with norms and a short stream, where the step-by-step kernel walks the updates
+                                   with norms and a short stream (direct norm sums of at most 4 W + 48
+                                   multiply-adds per element), where the step-by-step kernel walks the updates
                                    for the norms alone (direct sums are cheaper there than the Gram matrix)   */
     int32_t reserved;
     double fma_seq;       /* fused multiply-adds per element of the step-by-step evaluation                 */
@@ -426,6 +427,21 @@ star_status star_select_mode_ar(int32_t N, const double *iter_time, const double
  */
 star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_t *first_tile, int32_t *count,
                              int64_t *base);
+
+/*
+ * Host-only: the tiles of a short shard under a launch in queue order (the
+ * matrix-core kernel runs in that order at every length).  Up to 8 tiles per
+ * workgroup the queue's counter is not used at all: workgroup b of
+ * `workgroups` handles the consecutive tiles first_tile[b] .. first_tile[b] +
+ * count[b] - 1 = [b tiles / workgroups, (b+1) tiles / workgroups), an even
+ * split (counts differ by at most one) that covers every tile once.  With so
+ * few tiles the unequal first claims above would give some workgroups twice
+ * the work of others, and the counter's round trips would show in a kernel of
+ * a few microseconds.  first_tile and count hold `workgroups` entries.
+ * STAR_ERR_SHAPE for workgroups < 1 or tiles < 0, STAR_ERR_NULL for a NULL
+ * output.
+ */
+star_status star_plan_even_split(int32_t workgroups, int64_t tiles, int64_t *first_tile, int32_t *count);
 
 /* Bytes of internal device workspace one call of this shape uses. */
 size_t star_workspace_bytes(int64_t P, int32_t W, int32_t U);

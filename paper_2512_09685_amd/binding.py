@@ -103,6 +103,8 @@ def load_library():
     lib.star_group_gram.argtypes = [vp, ctypes.c_int, i64, i32, vp, vp]
     lib.star_group_gram_opt.restype = ctypes.c_int
     lib.star_group_gram_opt.argtypes = [vp, ctypes.c_int, i64, i32, vp, vp, vp]
+    lib.star_plan_even_split.restype = ctypes.c_int
+    lib.star_plan_even_split.argtypes = [i32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
     lib.star_plan_claims.restype = ctypes.c_int
     lib.star_plan_claims.argtypes = [i32, i32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.star_workspace_bytes.restype = ctypes.c_size_t
@@ -405,6 +407,14 @@ def star_select_mode_ar(iter_time, child_time, phi: float, batch_total: float, w
     if st != 0:
         raise StarError(st, "star_select_mode_ar rejected its arguments")
     return x.value, tw.value, ta.value, table
+
+
+def star_plan_even_split(workgroups: int, tiles: int):
+    """Host-only: (first_tile [G], count [G]) of a short shard's tiles under a launch in queue order."""
+    first = np.zeros(max(workgroups, 1), dtype=np.int64)
+    count = np.zeros(max(workgroups, 1), dtype=np.int32)
+    _check(load_library().star_plan_even_split(workgroups, ctypes.c_int64(tiles), first.ctypes.data, count.ctypes.data))
+    return first, count
 
 
 def star_plan_claims(workgroups: int, tiles_per_claim: int = 3):

@@ -291,7 +291,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     // direct sums, y_u + 1 multiply-adds per update, in the same pass as the collapsed update.
     if (update && want_norms && l.route == star::Route::Affine && !l.split_norms && opt.kernel == STAR_KERNEL_AUTO &&
         grad_dtype == STAR_F32 && l.Wp > 16 && plan.U <= star::seq_max_updates(l.Wp, true) &&
-        plan.fma_seq - 3.0 * plan.U <= star::kDirectNormFmas) {
+        plan.fma_seq - 3.0 * plan.U <= star::direct_norm_fma_limit(l.Wp)) {
         l.route = star::Route::Seq;
         l.collapsed_in_seq = true;
     }
@@ -864,6 +864,19 @@ star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_
         first_tile[b] = f.t0;
         count[b] = f.n;
         *base = (int64_t)f.base;
+    }
+    return STAR_OK;
+}
+
+star_status star_plan_even_split(int32_t workgroups, int64_t tiles, int64_t* first_tile, int32_t* count) {
+    g_err.clear();
+    if (workgroups < 1) return set_err(STAR_ERR_SHAPE, "workgroups must be positive");
+    if (tiles < 0) return set_err(STAR_ERR_SHAPE, "tiles is negative");
+    if (!first_tile || !count) return set_err(STAR_ERR_NULL, "an output pointer is NULL");
+    for (int32_t b = 0; b < workgroups; ++b) {
+        const star::FirstClaim f = star::first_claim_of(b, workgroups, -1, tiles);
+        first_tile[b] = f.t0;
+        count[b] = f.n;
     }
     return STAR_OK;
 }

@@ -178,29 +178,34 @@ __device__ __forceinline__ Span make_span(const int span_g, const int span_k, co
 // the same moments, every wave of the chip then walks the rows in step, and that pattern, once set,
 // persists through the kernel: the 32-row bf16 aggregation ran 70 % slower that way (2.77 against
 // 1.63 ms).  A spread of up to two tile times at the start is enough to keep the requests mixed.
-__device__ __forceinline__ FirstClaim first_claim(const int claim) {
-    return first_claim_of((int64_t)blockIdx.x, (int64_t)gridDim.x, claim);
+__device__ __forceinline__ FirstClaim first_claim(const int claim, const int64_t ntile) {
+    return first_claim_of((int64_t)blockIdx.x, (int64_t)gridDim.x, claim, ntile);
 }
 
 template <class Body>
 __device__ __forceinline__ void for_each_claimed_tile(TileQueue* __restrict__ q, const int64_t ntile, const int claim,
                                                       Body&& body) {
     __shared__ unsigned long long s_first;
-    const FirstClaim fc = first_claim(claim);
+    const FirstClaim fc = first_claim(claim, ntile);
+    const int step = claim < 0 ? -claim : claim;
+    // When the first claims already cover the shard nobody asks the counter, and nobody has to put it
+    // back: the same for every workgroup of the launch (base and ntile are).
+    const bool counter = fc.base < (unsigned long long)ntile;
     unsigned long long nxt = 0;
     int64_t t0 = fc.t0;
     int n = fc.n;
     while (t0 < ntile) {
-        if (threadIdx.x == 0) nxt = fc.base + atomicAdd(&q->next, (unsigned long long)claim);
+        if (counter && threadIdx.x == 0) nxt = fc.base + atomicAdd(&q->next, (unsigned long long)step);
         const int64_t t1 = t0 + n < ntile ? t0 + n : ntile;
-        n = claim;
+        n = step;
         for (int64_t t = t0; t < t1; ++t) body(t);
+        if (!counter) break;
         if (threadIdx.x == 0) s_first = nxt;
         __syncthreads();
         t0 = (int64_t)s_first;
         __syncthreads();   // everyone has read s_first before thread 0 writes it again
     }
-    if (threadIdx.x == 0) {
+    if (counter && threadIdx.x == 0) {
         // this workgroup's claims have all returned (their values were used above), so when the
         // count reaches the grid size nobody touches `next` any more
         const unsigned int left = atomicAdd(&q->done, 1u);
@@ -219,27 +224,33 @@ template <class Body>
 __device__ __forceinline__ void for_each_claimed_tile_ahead(TileQueue* __restrict__ q, const int64_t ntile,
                                                             const int claim, Body&& body) {
     __shared__ unsigned long long s_first;
-    const FirstClaim fc = first_claim(claim);
+    const FirstClaim fc = first_claim(claim, ntile);
+    const int step = claim < 0 ? -claim : claim;
     const unsigned long long base = fc.base;
+    const bool counter = base < (unsigned long long)ntile;   // see for_each_claimed_tile
     unsigned long long nxt = 0;
     int64_t cur = fc.t0;
-    if (cur < ntile) {
-        if (threadIdx.x == 0) nxt = base + atomicAdd(&q->next, (unsigned long long)claim);
+    if (cur < ntile && fc.n > 0) {   // (an even split of fewer tiles than workgroups leaves some without)
+        if (counter && threadIdx.x == 0) nxt = base + atomicAdd(&q->next, (unsigned long long)step);
         int64_t end = cur + fc.n < ntile ? cur + fc.n : ntile;
         for (;;) {
             int64_t following = cur + 1;
             if (following >= end) {   // last tile of this claim: where does the next one start?
-                if (threadIdx.x == 0) s_first = nxt;
-                __syncthreads();
-                following = (int64_t)s_first;
-                __syncthreads();
-                if (following < ntile) {
-                    // no claim is requested once the end is known: nothing may touch the queue
-                    // after this workgroup has reported that it left
-                    if (threadIdx.x == 0) nxt = base + atomicAdd(&q->next, (unsigned long long)claim);
-                    end = following + claim < ntile ? following + claim : ntile;
-                } else {
+                if (!counter) {
                     following = -1;
+                } else {
+                    if (threadIdx.x == 0) s_first = nxt;
+                    __syncthreads();
+                    following = (int64_t)s_first;
+                    __syncthreads();
+                    if (following < ntile) {
+                        // no claim is requested once the end is known: nothing may touch the queue
+                        // after this workgroup has reported that it left
+                        if (threadIdx.x == 0) nxt = base + atomicAdd(&q->next, (unsigned long long)step);
+                        end = following + step < ntile ? following + step : ntile;
+                    } else {
+                        following = -1;
+                    }
                 }
             }
             body(cur, following);
@@ -247,7 +258,7 @@ __device__ __forceinline__ void for_each_claimed_tile_ahead(TileQueue* __restric
             cur = following;
         }
     }
-    if (threadIdx.x == 0) {
+    if (counter && threadIdx.x == 0) {
         const unsigned int left = atomicAdd(&q->done, 1u);
         if (left + 1 == gridDim.x) {
             atomicExch(&q->next, 0ull);
@@ -289,9 +300,10 @@ struct Geometry {
 // tile per workgroup, dispatched in address order.
 // `thread_bytes`: bytes one thread has in flight per tile; long-lived workgroups are stacked on a compute unit
 // (up to `max_per_cu`) until about 64 KB per unit are in flight, which light bf16 kernels need and heavy fp32
-// ones already have with one workgroup.
+// ones already have with one workgroup; `min_per_cu` is for kernels that need a second workgroup per unit for
+// their arithmetic rather than for their memory traffic.
 inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int num_cu, int grid_cap,
-                              int thread_bytes = 256, int max_per_cu = 1) {
+                              int thread_bytes = 256, int max_per_cu = 1, int min_per_cu = 1) {
     const int64_t items = vec_ok ? std::max<int64_t>(P / vec, P % vec) : P;
     const int64_t tiles = std::max<int64_t>(1, (items + kBlock - 1) / kBlock);
     Geometry g;
@@ -299,7 +311,7 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
     g.threads = kBlock;
     if (reduces) {
         const int wg_bytes = std::max(1, thread_bytes) * kBlock;
-        const int bpc = std::max(1, std::min(max_per_cu, (64 * 1024 + wg_bytes - 1) / wg_bytes));
+        const int bpc = std::max(min_per_cu, std::min(max_per_cu, (64 * 1024 + wg_bytes - 1) / wg_bytes));
         g.span_g = (int)std::min<int64_t>(std::min(num_cu * bpc, grid_cap), tiles);
         g.span_k = 0x7fffffff;
         g.grid = g.span_g;
@@ -319,13 +331,21 @@ inline Geometry pick_geometry(int64_t P, int vec, bool vec_ok, bool reduces, int
 inline int queue_workgroups_per_cu(int thread_bytes, bool writes_state) {
     return writes_state && thread_bytes >= 128 ? 1 : 2;
 }
+// `tiles`: whole tiles of the shard if the launcher knows them (an estimate will do: the kernel splits
+// its own count).  Up to kShortTilesPerWorkgroup tiles per workgroup the launch takes the short-shard
+// form of the first claims (first_claim_of) and no more workgroups than tiles.
+constexpr int kShortTilesPerWorkgroup = 8;
 inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu, int thread_bytes,
-                               Traffic traffic = Traffic::Update) {
+                               Traffic traffic = Traffic::Update, int64_t tiles = -1) {
     Geometry g;
     g.threads = kBlock;
     g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));
     g.span_k = 0x7fffffff;
     g.claim = queue_claim(thread_bytes, traffic);
+    if (tiles >= 0 && tiles <= (int64_t)g.grid * kShortTilesPerWorkgroup) {
+        g.claim = -1;
+        g.grid = g.span_g = (int)std::max<int64_t>(1, std::min<int64_t>(g.grid, tiles));
+    }
     return g;
 }
 

@@ -62,12 +62,25 @@ constexpr int64_t kQueueMinElements = 16 << 20;
 
 // First round of claims (see for_each_claimed_tile): workgroup b of G gets 1 + b % claim tiles, laid out
 // one after the other from tile 0; the queue's counter hands out the tiles from `base` on.
+// A negative `claim` is the short-shard form: first claims that split all `ntile` tiles evenly between
+// the workgroups (consecutive tiles each, counts differ by at most one), so that nothing is left for
+// the counter and no workgroup waits for it.  With 2 to 8 tiles per workgroup the unequal first claims
+// and their granularity would leave some workgroups with twice the work of others, and a kernel of a
+// few microseconds would spend one or two of them on the counter's round trips.
 struct FirstClaim {
     int64_t t0;                // first tile of the workgroup's first claim
     int n;                     // tiles in it
     unsigned long long base;   // tiles covered by all first claims together
 };
-__host__ __device__ inline FirstClaim first_claim_of(const int64_t b, const int64_t G, const int claim) {
+__host__ __device__ inline FirstClaim first_claim_of(const int64_t b, const int64_t G, const int claim,
+                                                     const int64_t ntile = 0) {
+    if (claim < 0) {   // short shard: the tiles split evenly, workgroup b gets [b ntile / G, (b+1) ntile / G)
+        FirstClaim e;
+        e.t0 = b * ntile / G;
+        e.n = (int)((b + 1) * ntile / G - e.t0);
+        e.base = (unsigned long long)ntile;
+        return e;
+    }
     const int64_t per_group = (int64_t)claim * (claim + 1) / 2;   // tiles taken by `claim` consecutive workgroups
     const int64_t r = b % claim, rg = G % claim;
     FirstClaim f;
@@ -132,8 +145,11 @@ struct SeqArgs {
 // register-heavy Gram accumulators of more than kFewRows rows.
 inline bool seq_takes_queue(int updates_in_launch) { return updates_in_launch <= 2; }
 // Collapsed update with direct norms (step-by-step kernel's norm walk): for 17 to 32 fp32 rows, when the
-// stream's direct norm sums cost at most this many multiply-adds per element.
-constexpr double kDirectNormFmas = 320.0;
+// stream's direct norm sums cost at most this many multiply-adds per element.  Measured against the Gram
+// matrix on the matrix cores, 2 Mi and 64 Mi elements, 6 to 16 updates: the walk wins by 5-14 % up to about
+// 130 / 145 / 160 / 175 multiply-adds with 20 / 24 / 28 / 32 rows and loses beyond (at twice that by a third);
+// the limit grows with the rows because the matrix-core kernel's time does.
+inline double direct_norm_fma_limit(int Wp) { return 4.0 * Wp + 48.0; }
 inline bool aff_takes_queue(bool gram, int Wp) { return !gram || Wp <= kFewRows; }
 
 // Largest number of updates one launch of the step-by-step kernel accepts

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(star_[a-z_]+)\s*\(", header))
     assert {"star_group_update", "star_group_norms", "star_group_reduce", "star_group_update_publish", "star_group_gram",
-            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_plan_claims", "star_group_update_opt", "star_group_norms_opt",
+            "star_noise_scale", "star_select_mode_ps", "star_select_mode_ar", "star_plan_affine", "star_plan_choice", "star_plan_claims", "star_plan_even_split", "star_group_update_opt", "star_group_norms_opt",
             "star_group_reduce_opt", "star_group_gram_opt", "star_group_update_noalloc",
             "star_workspace_bytes", "star_last_error", "star_version", "star_shutdown"} <= names
     lib = star.load_library()
@@ -105,6 +105,24 @@ def test_first_round_of_claims_tiles_the_front_of_the_shard(G, claim):
     assert first[0] == 0 and (covered == 1).all() and int(count.sum()) == base
 
 
+@pytest.mark.parametrize("G", [1, 2, 7, 256, 512, 1000])
+def test_even_split_of_a_short_shard_covers_every_tile_once(G):
+    """Short shards in queue order: workgroup b handles tiles [b n / G, (b+1) n / G).  The ranges follow one
+    another without gap or overlap from tile 0 to tile n - 1 and their lengths differ by at most one, for
+    fewer tiles than workgroups too (some then get none)."""
+    for n in (0, 1, G - 1, G, G + 1, 3 * G + 5, 8 * G):
+        if n < 0:
+            continue
+        first, count = star.star_plan_even_split(G, n)
+        assert first[0] == 0 and int(first[-1]) + int(count[-1]) == n
+        assert np.array_equal(first[1:], first[:-1] + count[:-1])
+        assert count.min() >= 0 and count.max() - count.min() <= 1 and count.sum() == n
+    lib = star.load_library()
+    assert lib.star_plan_even_split(0, ctypes.c_int64(4), None, None) == 2
+    assert lib.star_plan_even_split(4, ctypes.c_int64(-1), None, None) == 2
+    assert lib.star_plan_even_split(4, ctypes.c_int64(4), None, None) == 1
+
+
 def test_plan_claims_validation():
     lib = star.load_library()
     assert lib.star_plan_claims(0, 3, None, None, None) == 2
@@ -183,13 +201,26 @@ def test_plan_choice_wide_fp32_rows_with_norms():
     (step-by-step kernel, one launch, queue order on long shards), a long one the Gram matrix on the matrix cores;
     bf16 rows, forced kernels and norms alone are not affected."""
     rng = np.random.default_rng(1)
-    offs, mem, _ = _rand_stream(rng, 32, 8)
+    # 8 groups of 16 of the 32 workers: 8 * 17 = 136 multiply-adds for the direct norm sums, limit 4 * 32 + 48
+    offs = np.arange(0, 129, 16, dtype=np.int32)
+    mem = np.concatenate([np.sort(rng.choice(32, 16, replace=False)) for _ in range(8)]).astype(np.int32)
     short = star.UpdateStream(offs, mem)
     hp = dict(lr=0.1, momentum_coef=0.9, want_norms=True)
     c = star.star_plan_choice(50_000_000, 32, "f32", short, **hp)
     assert (c["kernel"], c["collapsed_update"], c["launches"], c["finishing_launches"], c["queue_order"]) == \
         (star.KERNEL_SEQ, 1, 1, 1, 1)
-    assert c["fma_seq"] - 3 * 8 <= 320
+    assert c["fma_seq"] - 3 * 8 == 136
+    # the same groups twice over: 272 multiply-adds, beyond the limit
+    twice = star.UpdateStream(np.arange(0, 257, 16, dtype=np.int32), np.concatenate([mem, mem]))
+    assert star.star_plan_choice(50_000_000, 32, "f32", twice, **hp)["kernel"] == star.KERNEL_AFFINE_MFMA
+    # 20 rows: limit 128
+    offs20 = np.arange(0, 81, 10, dtype=np.int32)
+    mem20 = np.concatenate([np.sort(rng.choice(20, 10, replace=False)) for _ in range(8)]).astype(np.int32)
+    assert star.star_plan_choice(1 << 20, 20, "f32", star.UpdateStream(offs20, mem20), **hp)["kernel"] == star.KERNEL_SEQ
+    offs20 = np.arange(0, 8 * 16 + 1, 16, dtype=np.int32)
+    mem20 = np.concatenate([np.sort(rng.choice(20, 16, replace=False)) for _ in range(8)]).astype(np.int32)
+    assert star.star_plan_choice(1 << 20, 20, "f32", star.UpdateStream(offs20, mem20), **hp)["kernel"] == \
+        star.KERNEL_AFFINE_MFMA
     assert star.star_plan_choice(50_000_000, 32, "bf16", short, **hp)["kernel"] == star.KERNEL_AFFINE_MFMA
     assert star.star_plan_choice(50_000_000, 32, "f32", short, kernel=star.KERNEL_AFFINE_MFMA, **hp)["kernel"] == \
         star.KERNEL_AFFINE_MFMA
