@@ -423,19 +423,21 @@ __global__ __launch_bounds__(kBlock) void seq_kernel(float* __restrict__ params,
 __global__ __launch_bounds__(kBlock) void reduce_kernel(const double* __restrict__ partials, const int grid,
                                                         double* __restrict__ sums_out,
                                                         float* __restrict__ sqrt_out) {
-    __shared__ double s_part[kBlock];
+    __shared__ double s_wave[kBlock / 64];
     const int e = blockIdx.x;
     double s = 0.0;
     for (int b = threadIdx.x; b < grid; b += kBlock) s += partials[(int64_t)e * grid + b];
-    s_part[threadIdx.x] = s;
+    // fixed order: within a wave by the cross-lane moves, then the waves in turn (these kernels last a
+    // few microseconds, most of it latency, so one barrier instead of a tree of eight)
+    s = wave_sum_to_lane63(s);
+    if ((threadIdx.x & 63) == 63) s_wave[threadIdx.x >> 6] = s;
     __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
-        __syncthreads();
-    }
     if (threadIdx.x == 0) {
-        if (sums_out) sums_out[e] = s_part[0];
-        if (sqrt_out) sqrt_out[e] = (float)sqrt(s_part[0]);
+        double t = 0.0;
+#pragma unroll
+        for (int q = 0; q < kBlock / 64; ++q) t += s_wave[q];
+        if (sums_out) sums_out[e] = t;
+        if (sqrt_out) sqrt_out[e] = (float)sqrt(t);
     }
 }
 
@@ -444,33 +446,37 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const double* __restrict
 __global__ __launch_bounds__(kBlock) void gram_norms_kernel(const double* __restrict__ gamma,
                                                             const double* __restrict__ coef, const int U,
                                                             const int W, float* __restrict__ norms_out) {
-    __shared__ double s_part[kBlock];
+    __shared__ double s_wave[kBlock / 64];
     const int u = blockIdx.x;
     const double* c = coef + (int64_t)u * W;
     const int ng = W * (W + 1) / 2;
     double s = 0.0;
     for (int e = threadIdx.x; e < ng; e += kBlock) {
+        const double g = gamma[e];   // requested together with the coefficients: one memory latency, not two
         int a = 0, rem = e;
         while (rem >= W - a) {
             rem -= W - a;
             ++a;
         }
         const int b = a + rem;
+        const double ca = c[a], cb = c[b];
         // rows outside the group take no part: a non-finite entry of a worker that is not a member (0 * inf)
         // must not reach this group's norm
-        if (c[a] == 0.0 || c[b] == 0.0) continue;
-        const double t = c[a] * c[b] * gamma[e];
+        if (ca == 0.0 || cb == 0.0) continue;
+        const double t = ca * cb * g;
         s += (a == b) ? t : 2.0 * t;
     }
-    s_part[threadIdx.x] = s;
+    s = wave_sum_to_lane63(s);
+    if ((threadIdx.x & 63) == 63) s_wave[threadIdx.x >> 6] = s;
     __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
-        __syncthreads();
-    }
     // a tiny negative sum (rounding of a quadratic form that is zero) gives 0; a non-finite one stays
     // non-finite, so that a bad gradient report shows in the norms of the groups it is part of
-    if (threadIdx.x == 0 && u < U) norms_out[u] = (float)sqrt(s_part[0] < 0.0 && s_part[0] > -1e300 ? 0.0 : s_part[0]);
+    if (threadIdx.x == 0 && u < U) {
+        double t = 0.0;
+#pragma unroll
+        for (int q = 0; q < kBlock / 64; ++q) t += s_wave[q];
+        norms_out[u] = (float)sqrt(t < 0.0 && t > -1e300 ? 0.0 : t);
+    }
 }
 
 // Packed upper triangle (row-major, a <= b) -> full symmetric W x W matrix; a zero
