@@ -102,8 +102,10 @@ typedef enum {
 typedef enum {
     STAR_KERNEL_AUTO = 0,  /* the library chooses (star_plan_choice tells what): a single update on fp32
                               rows SEQ, otherwise the collapsed map; with norms the Gram matrix on the
-                              matrix cores (up to 6 rows: vector registers), except that coefficients of
-                              both signs and short streams on 17 to 32 fp32 rows get direct norm sums     */
+                              matrix cores (vector registers instead: up to 6 rows, and 7 or 8 rows below
+                              16 Mi elements; but 3 to 8 bf16 rows up to 8 Mi elements: matrix cores),
+                              except that coefficients of both signs and short streams on 17 to 32 fp32
+                              rows get direct norm sums                                                  */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers; norms from direct sums of
                               gbar_u^2                                                                   */
     STAR_KERNEL_AFFINE = 2, /* the U updates collapsed into one affine map of (p, v, g_0..g_W-1); the Gram
@@ -431,7 +433,8 @@ star_status star_plan_claims(int32_t workgroups, int32_t tiles_per_claim, int64_
 /*
  * Host-only: the tiles of a short shard under a launch in queue order (the
  * matrix-core kernel runs in that order at every length).  Up to 8 tiles per
- * workgroup the queue's counter is not used at all: workgroup b of
+ * workgroup (16 with light tiles; 48 or 128 for launches that only read: norms
+ * or Gram matrix alone) the queue's counter is not used at all: workgroup b of
  * `workgroups` handles the consecutive tiles first_tile[b] .. first_tile[b] +
  * count[b] - 1 = [b tiles / workgroups, (b+1) tiles / workgroups), an even
  * split (counts differ by at most one) that covers every tile once.  With so

@@ -239,18 +239,34 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
 // accumulators there and takes its tiles from the queue as well (norms on, 8 updates: 1 fp32 row 0.34
 // against 0.49 ms on 100 M elements, 4 rows 0.53 against 0.64; 1 bf16 row 0.59 against 0.66 ms on 200 M
 // elements; 6 rows equal, 7 and 8 rows 2-6 % behind).
-// Without the update (norms alone, the Gram matrix alone) the state's 32 bytes per thread are missing and a
-// tile of few bf16 rows is so light that the vector-register form's per-chunk work shows: there the matrix
-// cores are ahead from 4 rows on (134 M elements, 4 / 5 / 6 bf16 rows: 0.57 / 0.65 / 0.71 of the HBM peak
-// against 0.48 / 0.55 / 0.43; fp32 rows: 0.46 / 0.56 / 0.65 against 0.80 / 0.82 / 0.65).
+// Without the update (norms alone, the Gram matrix alone) the rule is a different one, see the function.
 // On shards below 16 Mi elements an update with norms on 7 or 8 rows is faster with the vector-register form and
 // its fixed assignment as well (36 accumulators still leave room): 1 Mi elements 21 against 28 us, 8 Mi 80
 // against 89 us, equal at 16 Mi; 16 rows are faster on the matrix cores at every length.
+// 3 to 8 bf16 rows are the exception to the exception: up to 8 Mi elements the matrix-core kernel splits its
+// tiles evenly over the workgroups instead of claiming them (queue_geometry), and with tiles that light it is
+// then 5-16 % ahead of the vector-register form (6 rows: 2 / 4 / 8 Mi elements 20 / 30 / 50 against 24 / 36 / 60 us);
+// 5 and 6 rows keep that lead up to 16 Mi elements (6 rows: 95 against 106 us), from 48 Mi on the two are equal.
 bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update, int64_t P) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
     if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
-    if (!update && grad_dtype == STAR_BF16) return Wp >= 4;
+    if (!update) {
+        // norms or Gram matrix alone (a pure read).  fp32 rows: up to 8 on the vector ALUs, whose long-lived
+        // workgroups with a fixed assignment reach 0.80-0.88 of the HBM peak there, while the matrix instructions
+        // cost as much for 7 rows as for 16 (96 Mi elements, 7 / 8 rows: 400 / 458 against 497 / 545 us; 12 rows
+        // equal).  bf16 rows: the light tiles of 3 to 6 rows are faster on the matrix-core kernel while it splits
+        // its tiles evenly (12 Mi elements, 3 / 4 / 6 rows: 30 / 31 / 34 against 39 / 44 / 54 us) and slower on
+        // long shards, where the vector-register form loads several chunks per thread (96 Mi elements, 4 / 5 / 6
+        // rows: 141 / 167 / 201 against 182 / 197 / 211 us); from 7 rows on the matrix cores at every length.
+        if (grad_dtype == STAR_F32) return Wp > 8;
+        if (Wp >= 7) return true;
+        if (Wp >= 5) return P <= (48 << 20);
+        if (Wp >= 3) return P <= (16 << 20);
+        return false;
+    }
+    if (update && grad_dtype == STAR_BF16 && Wp >= 3 && Wp <= 8 && P <= (8 << 20)) return true;
+    if (update && grad_dtype == STAR_BF16 && (Wp == 5 || Wp == 6) && P <= (16 << 20)) return true;
     if (update && Wp <= 8 && P < star::kQueueMinElements) return false;
     return Wp > star::kFewRows;
 }

@@ -332,9 +332,20 @@ inline int queue_workgroups_per_cu(int thread_bytes, bool writes_state) {
     return writes_state && thread_bytes >= 128 ? 1 : 2;
 }
 // `tiles`: whole tiles of the shard if the launcher knows them (an estimate will do: the kernel splits
-// its own count).  Up to kShortTilesPerWorkgroup tiles per workgroup the launch takes the short-shard
-// form of the first claims (first_claim_of) and no more workgroups than tiles.
-constexpr int kShortTilesPerWorkgroup = 8;
+// its own count).  Up to short_tiles_per_workgroup() tiles per workgroup the launch takes the short-shard
+// form of the first claims (first_claim_of) and no more workgroups than tiles.  Where the queue's order
+// starts to pay, measured on the matrix-core kernel (the one that is in queue order at every length):
+//   update with norms   8 tiles per workgroup (16 fp32 rows, 1 Mi elements: 27 against 34 us; 16 tiles: equal
+//                       with one workgroup per unit, 2-7 % behind with two; 32 tiles: 10 % behind);
+//                       16 tiles when a thread moves less than 160 bytes per tile (4 to 12 bf16 rows,
+//                       6 and 8 Mi elements: 5-16 % ahead of 8)
+//   norms / Gram alone  a pure read: 48 tiles (12 to 24 Mi elements: 2-10 % ahead of the queue, 32 Mi
+//                       and more: 1-3 % behind with 16 to 32 rows); 128 tiles up to 128 bytes per thread and
+//                       tile (8 bf16 rows, 16 to 64 Mi elements: 7-15 % ahead)
+inline int short_tiles_per_workgroup(int thread_bytes, Traffic traffic) {
+    if (traffic == Traffic::ReadOnly) return thread_bytes <= 128 ? 128 : 48;
+    return thread_bytes < 160 ? 16 : 8;
+}
 inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu, int thread_bytes,
                                Traffic traffic = Traffic::Update, int64_t tiles = -1) {
     Geometry g;
@@ -342,7 +353,7 @@ inline Geometry queue_geometry(int num_cu, int grid_cap, int per_cu, int thread_
     g.grid = g.span_g = std::max(1, std::min(num_cu * per_cu, grid_cap));
     g.span_k = 0x7fffffff;
     g.claim = queue_claim(thread_bytes, traffic);
-    if (tiles >= 0 && tiles <= (int64_t)g.grid * kShortTilesPerWorkgroup) {
+    if (tiles >= 0 && tiles <= (int64_t)g.grid * short_tiles_per_workgroup(thread_bytes, traffic)) {
         g.claim = -1;
         g.grid = g.span_g = (int)std::max<int64_t>(1, std::min<int64_t>(g.grid, tiles));
     }

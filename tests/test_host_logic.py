@@ -236,6 +236,26 @@ def test_plan_choice_wide_fp32_rows_with_norms():
         star.KERNEL_AFFINE_MFMA
 
 
+def test_plan_choice_gram_route_for_few_rows():
+    """Where the Gram matrix is formed when AUTO decides (measured crossovers, see gram_on_matrix_cores)."""
+    def route(P, W, dt, update):
+        us = star.UpdateStream(np.array([0, W, 2 * W], np.int32), np.tile(np.arange(W, dtype=np.int32), 2))
+        c = star.star_plan_choice(P, W, dt, us, lr=0.1, momentum_coef=0.9, update=update, want_norms=True)
+        return {star.KERNEL_AFFINE: "valu", star.KERNEL_AFFINE_MFMA: "mfma"}[c["kernel"]]
+    Mi = 1 << 20
+    # update with norms
+    assert [route(4 * Mi, W, "f32", True) for W in (2, 6, 7, 8, 9, 16)] == ["valu"] * 4 + ["mfma"] * 2
+    assert [route(64 * Mi, W, "f32", True) for W in (2, 6, 7, 8, 9)] == ["valu"] * 2 + ["mfma"] * 3
+    assert [route(4 * Mi, W, "bf16", True) for W in (2, 3, 6, 8, 9)] == ["valu"] + ["mfma"] * 4
+    assert [route(12 * Mi, W, "bf16", True) for W in (3, 4, 5, 6, 7, 8, 9)] == ["valu"] * 2 + ["mfma"] * 2 + ["valu"] * 2 + ["mfma"]
+    assert [route(64 * Mi, W, "bf16", True) for W in (3, 6, 7, 8)] == ["valu"] * 2 + ["mfma"] * 2
+    # norms alone
+    assert [route(P, W, "f32", False) for P in (Mi, 96 * Mi) for W in (4, 8, 9, 16)] == ["valu", "valu", "mfma", "mfma"] * 2
+    assert [route(12 * Mi, W, "bf16", False) for W in (2, 3, 4, 6, 7)] == ["valu"] + ["mfma"] * 4
+    assert [route(32 * Mi, W, "bf16", False) for W in (2, 3, 4, 5, 6, 7)] == ["valu"] * 3 + ["mfma"] * 3
+    assert [route(96 * Mi, W, "bf16", False) for W in (4, 5, 6, 7, 16)] == ["valu"] * 3 + ["mfma"] * 2
+
+
 def test_plan_choice_direct_norms_option():
     """STAR_OPT_DIRECT_NORMS: the update stays collapsed and gets a direct norm pass beside it (one more
     launch over the rows and its finishing launch instead of the Gram matrix's two); norms alone go to the
@@ -280,7 +300,8 @@ def test_plan_choice_reports_the_kernels_of_the_five_workloads():
         assert c1["kernel"] == (star.KERNEL_SEQ if wl.grad_dtype == "f32" else star.KERNEL_AFFINE)
         # norms alone
         cn = star.star_plan_choice(wl.P, wl.W, wl.grad_dtype, us, wmode=wl.wmode, update=False, want_norms=True)
-        assert cn["kernel"] == (star.KERNEL_AFFINE if wl.W <= 6 else star.KERNEL_AFFINE_MFMA)
+        valu = wl.W <= 8 if wl.grad_dtype == "f32" else wl.W <= 2      # (the five have 4, 8, 16 fp32 and 16, 32 bf16 rows)
+        assert cn["kernel"] == (star.KERNEL_AFFINE if valu else star.KERNEL_AFFINE_MFMA)
 
 
 def test_workspace_bytes_is_modest():
