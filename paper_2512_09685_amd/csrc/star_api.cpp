@@ -314,7 +314,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     if (l.route == star::Route::Affine) {
         const bool gram = want_norms;
         l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update, P);
-        l.queue_order = l.mfma || (l.want_queue && star::aff_takes_queue(gram, l.Wp));
+        l.queue_order = l.mfma || (l.want_queue && star::aff_takes_queue(gram, l.Wp, grad_dtype == STAR_F32, update));
         l.launches = (update || gram) ? 1 : 0;
         l.finishing = gram ? 2 : 0;
     } else {

@@ -150,7 +150,17 @@ inline bool seq_takes_queue(int updates_in_launch) { return updates_in_launch <=
 // 130 / 145 / 160 / 175 multiply-adds with 20 / 24 / 28 / 32 rows and loses beyond (at twice that by a third);
 // the limit grows with the rows because the matrix-core kernel's time does.
 inline double direct_norm_fma_limit(int Wp) { return 4.0 * Wp + 48.0; }
-inline bool aff_takes_queue(bool gram, int Wp) { return !gram || Wp <= kFewRows; }
+// Which Gram launches of the collapsed kernel use the few-rows form (double fold slots in LDS after every
+// chunk, tiles from the queue on long shards): up to kFewRows rows -- except the Gram matrix alone on exactly
+// kFewRows fp32 rows, whose 21 slot updates per chunk are not hidden by 96 bytes of loads (32 to 96 Mi
+// elements: 0.57-0.65 of the HBM peak, against 0.82 with 5 rows and 0.85 with 7); that one takes the form
+// of the larger row counts (fp32 slots folded every kGramFold tiles, fixed assignment).
+constexpr bool gram_few_rows_form(int Wp, bool f32_rows, bool update) {
+    return Wp <= kFewRows && !(Wp == kFewRows && f32_rows && !update);
+}
+inline bool aff_takes_queue(bool gram, int Wp, bool f32_rows, bool update) {
+    return !gram || gram_few_rows_form(Wp, f32_rows, update);
+}
 
 // Largest number of updates one launch of the step-by-step kernel accepts
 // (bounded by the LDS tables and, with norms, the per-thread accumulators).

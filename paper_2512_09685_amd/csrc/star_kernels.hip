@@ -71,7 +71,7 @@ void aff_kernel(float* __restrict__ params, float* __restrict__ momentum,
     // With few rows (up to kFewRows) there are few pairs: the slots are double and take the sums after
     // every chunk, which makes them independent of the order of the tiles (to 1e-16), so that this
     // variant can take its tiles from the queue like the plain one; and it has the registers for it.
-    constexpr bool kFew = GRAM && W <= kFewRows;
+    constexpr bool kFew = GRAM && gram_few_rows_form(W, std::is_same<R, RowF32>::value, UPDATE);
     typedef typename std::conditional<kFew, double, float>::type fold_t;
     __shared__ fold_t fold[GRAM ? NG * kBlock : 1];
     if constexpr (GRAM) {
@@ -540,7 +540,7 @@ hipError_t launch_aff_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_ou
     // chunk; 1 / 2 / 3 bf16 rows with 4 / 4 / 2 chunks: 0.44 / 0.66 / 0.65 against 0.22 / 0.36 / 0.48)
     constexpr int KCH = (GRAM && !UPDATE && W <= kFewRows && kRowBytes < 64)
                             ? (kRowBytes <= 8 ? 8 : (kRowBytes <= 16 ? 4 : 2)) : 1;
-    const bool queued = aff_takes_queue(GRAM, W) && a.queue && a.vec_ok;
+    const bool queued = aff_takes_queue(GRAM, W, std::is_same<R, RowF32>::value, UPDATE) && a.queue && a.vec_ok;
     if constexpr (KCH > 1) {
         if (queued) {
             const int thread_bytes = kRowBytes * KCH;
