@@ -103,7 +103,8 @@ typedef enum {
     STAR_KERNEL_AUTO = 0,  /* the library chooses (star_plan_choice tells what): a single update on fp32
                               rows SEQ, otherwise the collapsed map; with norms the Gram matrix on the
                               matrix cores (vector registers instead: up to 6 rows, and 7 or 8 rows below
-                              16 Mi elements; but 3 to 8 bf16 rows up to 8 Mi elements: matrix cores),
+                              16 Mi elements; but 3 to 8 bf16 rows up to 8 Mi elements, and most shards of 4 to
+                              6 bf16 rows below 48 Mi: matrix cores),
                               except that coefficients of both signs and short streams on 17 to 32 fp32
                               rows get direct norm sums                                                  */
     STAR_KERNEL_SEQ = 1,   /* update by update, gradients held in registers; norms from direct sums of

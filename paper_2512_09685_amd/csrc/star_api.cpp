@@ -246,7 +246,9 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
 // 3 to 8 bf16 rows are the exception to the exception: up to 8 Mi elements the matrix-core kernel splits its
 // tiles evenly over the workgroups instead of claiming them (queue_geometry), and with tiles that light it is
 // then 5-16 % ahead of the vector-register form (6 rows: 2 / 4 / 8 Mi elements 20 / 30 / 50 against 24 / 36 / 60 us);
-// 5 and 6 rows keep that lead up to 16 Mi elements (6 rows: 95 against 106 us), from 48 Mi on the two are equal.
+// 5 and 6 rows keep that lead until the vector-register form takes the queue at 48 Mi elements (6 rows, 16 / 32 / 40 Mi:
+// 95 / 172 / 211 against 106 / 197 / 244 us; equal from 48 Mi on), 4 rows have it again from 16 Mi on (32 Mi: 153
+// against 160 us; at 12 Mi the vector-register form is 4 % ahead).
 bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update, int64_t P) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
@@ -266,7 +268,8 @@ bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update, int64
         return false;
     }
     if (update && grad_dtype == STAR_BF16 && Wp >= 3 && Wp <= 8 && P <= (8 << 20)) return true;
-    if (update && grad_dtype == STAR_BF16 && (Wp == 5 || Wp == 6) && P <= (16 << 20)) return true;
+    if (update && grad_dtype == STAR_BF16 && Wp >= 4 && Wp <= 6 && P < 3 * star::kQueueMinElements)
+        return Wp >= 5 || P >= (16 << 20);
     if (update && Wp <= 8 && P < star::kQueueMinElements) return false;
     return Wp > star::kFewRows;
 }

@@ -248,7 +248,8 @@ def test_plan_choice_gram_route_for_few_rows():
     assert [route(64 * Mi, W, "f32", True) for W in (2, 6, 7, 8, 9)] == ["valu"] * 2 + ["mfma"] * 3
     assert [route(4 * Mi, W, "bf16", True) for W in (2, 3, 6, 8, 9)] == ["valu"] + ["mfma"] * 4
     assert [route(12 * Mi, W, "bf16", True) for W in (3, 4, 5, 6, 7, 8, 9)] == ["valu"] * 2 + ["mfma"] * 2 + ["valu"] * 2 + ["mfma"]
-    assert [route(64 * Mi, W, "bf16", True) for W in (3, 6, 7, 8)] == ["valu"] * 2 + ["mfma"] * 2
+    assert [route(32 * Mi, W, "bf16", True) for W in (3, 4, 5, 6, 7, 8)] == ["valu"] + ["mfma"] * 5
+    assert [route(64 * Mi, W, "bf16", True) for W in (3, 4, 6, 7, 8)] == ["valu"] * 3 + ["mfma"] * 2
     # norms alone
     assert [route(P, W, "f32", False) for P in (Mi, 96 * Mi) for W in (4, 8, 9, 16)] == ["valu", "valu", "mfma", "mfma"] * 2
     assert [route(12 * Mi, W, "bf16", False) for W in (2, 3, 4, 6, 7)] == ["valu"] + ["mfma"] * 4
