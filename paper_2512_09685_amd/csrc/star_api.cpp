@@ -57,9 +57,18 @@ struct Opts {
 // 2-96 Mi elements, 16 updates, that is from about 16 Mi elements on with 8 and more fp32 rows (16 Mi: 0.76
 // against 0.66 of the HBM peak with 8 rows, equal with 16), from about 32 Mi with up to 4 fp32 rows, and from
 // about 48 Mi with bf16 rows, whose tiles are half as heavy (16-32 Mi: the fixed assignment is 0-14 % ahead,
-// 64 Mi and more: the queue 2-8 %).  The launches without update keep 16 Mi.
-int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update) {
+// 64 Mi and more: the queue 2-8 %).  Norms and Gram matrix alone keep 16 Mi (few rows, vector registers: at 8 Mi
+// the fixed assignment is 5-25 % ahead, from 24 Mi on the queue, whose tiles hold several chunks per thread, by
+// 10 % to 4x).  The aggregation, a read of W rows with one row written, is faster with the fixed assignment far
+// longer: 4-48 Mi elements 2-25 % ahead for every row count and dtype, equal from about 96 Mi on with 16 and more
+// rows (the queue 2-3 % ahead from 96-144 Mi), and with light tiles -- up to 8 bf16 or 4 fp32 rows -- ahead at
+// every length tried (256 Mi elements, 4 / 8 bf16 rows: 480 / 808 against 622 / 876 us).
+int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update, bool aggregation = false) {
     if (opt.queue_min > 0) return opt.queue_min;
+    if (aggregation) {
+        const int row_bytes = rows * (grad_dtype == STAR_F32 ? 16 : 8);   // per thread and tile
+        return row_bytes <= 64 ? (int64_t)1 << 62 : 4 * star::kQueueMinElements;
+    }
     if (!update) return star::kQueueMinElements;
     if (grad_dtype == STAR_BF16) return 3 * star::kQueueMinElements;
     return rows <= 4 ? 2 * star::kQueueMinElements : star::kQueueMinElements;
@@ -657,7 +666,7 @@ star_status run_reduce(void* const* out_rows, int out_dtype, const void* const* 
         a.vec_ok = vec_ok ? 1 : 0;
         a.norms = want_norms ? 1 : 0;
         a.partials = slot->partials;
-        a.queue = P >= queue_min_for(opt, grad_dtype, Wc, false) ? slot->queue : nullptr;
+        a.queue = P >= queue_min_for(opt, grad_dtype, Wc, false, true) ? slot->queue : nullptr;
         int grid = 0;
         hipError_t e = star::launch_group_reduce(Wp, grad_dtype, a, num_cu, grid_cap, &grid, stream);
         if (e != hipSuccess) return hip_fail(e, "launch of the aggregation kernel");
