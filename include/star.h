@@ -101,7 +101,9 @@ typedef enum {
  * to fp32 rounding; see star_plan_affine). */
 typedef enum {
     STAR_KERNEL_AUTO = 0,  /* the library chooses (star_plan_choice tells what): a single update on fp32
-                              rows SEQ, otherwise the collapsed map; with norms the Gram matrix on the
+                              rows SEQ, and with norms any stream of up to 48 multiply-adds per element
+                              on a short shard (4 Mi elements, bf16 rows 16 Mi; 17 to 32 fp32 rows: 112,
+                              any length); otherwise the collapsed map; with norms the Gram matrix on the
                               matrix cores (vector registers instead: up to 6 rows, and 7 or 8 rows below
                               16 Mi elements; but 3 to 8 bf16 rows up to 8 Mi elements, and most shards of 4 to
                               6 bf16 rows below 48 Mi: matrix cores),

@@ -314,6 +314,26 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     }
     l.Wp = star::padded_rows(plan.Wc);
     l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update);
+    // Update with norms, a stream so short that walking it costs next to nothing (fma_seq, the sum of y_u + 4 over
+    // the updates): the literal kernel forms its norms directly, in the same pass, and needs one finishing launch
+    // where the Gram route needs two.  On a short shard that launch is most of the difference (1 Mi elements:
+    // 2 updates of 8 fp32 rows 14.5 against 20.1 us, one update of 32 bf16 rows 23 against 33 us; 4 Mi: 41 against
+    // 46, 69 against 80 us; from 16 Mi on the collapsed kernel is level or ahead, at 64 Mi by up to 40 %).  With 17
+    // to 32 fp32 rows the alternative is dearer -- the matrix cores' fp32 Gram matrix, or the collapsed update
+    // with the norm walk -- and the literal kernel stays ahead at every length up to about 110 multiply-adds
+    // (3 updates of 32 rows, 16 / 64 Mi elements: 438 / 1752 against 446 / 1953 us; 4 updates: 515 against 441).
+    // (Its norms are direct sums, so streams that were given a direct norm pass above are served as well.)
+    if (update && want_norms && l.route == star::Route::Affine && opt.kernel == STAR_KERNEL_AUTO &&
+        plan.U <= star::seq_max_updates(l.Wp, true)) {
+        const bool wide_f32 = grad_dtype == STAR_F32 && l.Wp > 16;
+        // (bf16 rows: up to 16 Mi elements -- there the literal kernel is still 4-12 % ahead with 2, 8 and 32 rows
+        // and level with 16; fp32 rows are level or 4 % behind at 16 Mi)
+        const int64_t short_shard = grad_dtype == STAR_BF16 ? (16 << 20) : (4 << 20);
+        if ((P <= short_shard && plan.fma_seq <= 48.0) || (wide_f32 && plan.fma_seq <= 112.0)) {
+            l.route = star::Route::Seq;
+            l.split_norms = false;
+        }
+    }
     // 17 to 32 fp32 rows, update with norms: the Gram matrix needs the fp32 matrix instructions (1536 flops per
     // element, only partly hidden: 0.60-0.64 of the HBM peak).  A short stream gets its norms cheaper from the
     // direct sums, y_u + 1 multiply-adds per update, in the same pass as the collapsed update.

@@ -239,9 +239,9 @@ def test_plan_choice_wide_fp32_rows_with_norms():
 def test_plan_choice_gram_route_for_few_rows():
     """Where the Gram matrix is formed when AUTO decides (measured crossovers, see gram_on_matrix_cores)."""
     def route(P, W, dt, update):
-        us = star.UpdateStream(np.array([0, W, 2 * W], np.int32), np.tile(np.arange(W, dtype=np.int32), 2))
+        us = star.UpdateStream(np.arange(0, 16 * W + 1, W, dtype=np.int32), np.tile(np.arange(W, dtype=np.int32), 16))
         c = star.star_plan_choice(P, W, dt, us, lr=0.1, momentum_coef=0.9, update=update, want_norms=True)
-        return {star.KERNEL_AFFINE: "valu", star.KERNEL_AFFINE_MFMA: "mfma"}[c["kernel"]]
+        return {star.KERNEL_AFFINE: "valu", star.KERNEL_AFFINE_MFMA: "mfma"}[c["kernel"]]   # (16 updates: not a stream for the literal kernel)
     Mi = 1 << 20
     # update with norms
     assert [route(4 * Mi, W, "f32", True) for W in (2, 6, 7, 8, 9, 16)] == ["valu"] * 4 + ["mfma"] * 2
@@ -257,6 +257,31 @@ def test_plan_choice_gram_route_for_few_rows():
     assert [route(96 * Mi, W, "bf16", False) for W in (4, 5, 6, 7, 16)] == ["valu"] * 3 + ["mfma"] * 2
 
 
+def test_plan_choice_short_streams_with_norms_take_the_literal_kernel():
+    """Update with norms: up to 48 multiply-adds of stream (sum of y_u + 4) on a shard of up to 4 Mi elements (bf16
+    rows: 16 Mi) the literal kernel (direct norms in the same pass, one finishing launch); with 17 to 32 fp32 rows up to 112
+    multiply-adds at every length."""
+    def choice(P, W, dt, U, norms=True):
+        us = star.UpdateStream(np.arange(0, U * W + 1, W, dtype=np.int32), np.tile(np.arange(W, dtype=np.int32), U))
+        return star.star_plan_choice(P, W, dt, us, lr=0.1, momentum_coef=0.9, want_norms=norms)
+    Mi = 1 << 20
+    for dt in ("f32", "bf16"):
+        c = choice(Mi, 8, dt, 2)                       # 24 multiply-adds
+        assert (c["kernel"], c["collapsed_update"], c["launches"], c["finishing_launches"]) == (star.KERNEL_SEQ, 0, 1, 1)
+        assert choice(4 * Mi, 8, dt, 4)["kernel"] == star.KERNEL_SEQ          # 48
+        assert choice(4 * Mi, 8, dt, 5)["kernel"] != star.KERNEL_SEQ          # 60
+        assert choice((5 if dt == "f32" else 17) * Mi, 8, dt, 2)["kernel"] != star.KERNEL_SEQ    # too long a shard
+    assert choice(16 * Mi, 8, "bf16", 2)["kernel"] == star.KERNEL_SEQ         # (bf16 rows: up to 16 Mi elements)
+    assert choice(Mi, 32, "bf16", 1)["kernel"] == star.KERNEL_SEQ             # 36
+    assert choice(Mi, 8, "bf16", 2, norms=False)["kernel"] == star.KERNEL_AFFINE
+    # wide fp32 rows
+    c = choice(64 * Mi, 32, "f32", 3)                  # 108: literal
+    assert c["kernel"] == star.KERNEL_SEQ and c["collapsed_update"] == 0
+    c = choice(64 * Mi, 32, "f32", 4)                  # 144: collapsed update with the norm walk (limit 4 * 32 + 48 on y_u + 1)
+    assert c["kernel"] == star.KERNEL_SEQ and c["collapsed_update"] == 1
+    assert choice(64 * Mi, 32, "bf16", 3)["kernel"] == star.KERNEL_AFFINE_MFMA
+
+
 def test_plan_choice_direct_norms_option():
     """STAR_OPT_DIRECT_NORMS: the update stays collapsed and gets a direct norm pass beside it (one more
     launch over the rows and its finishing launch instead of the Gram matrix's two); norms alone go to the
@@ -264,19 +289,19 @@ def test_plan_choice_direct_norms_option():
     us = star.UpdateStream(np.arange(0, 17, 2, dtype=np.int32), np.tile(np.arange(8, dtype=np.int32), 2))   # 8 groups of 2
     hp = dict(lr=0.1, momentum_coef=0.9)
     for dt in ("f32", "bf16"):
-        gram = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, **hp)
-        direct = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, direct_norms=True, **hp)
+        gram = star.star_plan_choice(24 << 20, 8, dt, us, want_norms=True, **hp)
+        direct = star.star_plan_choice(24 << 20, 8, dt, us, want_norms=True, direct_norms=True, **hp)
         assert gram["kernel"] in (star.KERNEL_AFFINE, star.KERNEL_AFFINE_MFMA) and gram["launches"] == 1
         assert gram["finishing_launches"] == 2
         assert direct["kernel"] == star.KERNEL_AFFINE and direct["collapsed_update"] == 1
         assert direct["launches"] == 2 and direct["finishing_launches"] == 1
-        alone = star.star_plan_choice(1 << 20, 8, dt, us, update=False, want_norms=True, direct_norms=True, **hp)
+        alone = star.star_plan_choice(24 << 20, 8, dt, us, update=False, want_norms=True, direct_norms=True, **hp)
         assert alone["kernel"] == star.KERNEL_SEQ
-        forced = star.star_plan_choice(1 << 20, 8, dt, us, want_norms=True, direct_norms=True,
+        forced = star.star_plan_choice(24 << 20, 8, dt, us, want_norms=True, direct_norms=True,
                                        kernel=star.KERNEL_AFFINE_MFMA, **hp)
         assert forced["kernel"] == star.KERNEL_AFFINE_MFMA and forced["launches"] == 1
-        plain = star.star_plan_choice(1 << 20, 8, dt, us, direct_norms=True, **hp)
-        assert plain == star.star_plan_choice(1 << 20, 8, dt, us, **hp)
+        plain = star.star_plan_choice(24 << 20, 8, dt, us, direct_norms=True, **hp)
+        assert plain == star.star_plan_choice(24 << 20, 8, dt, us, **hp)
 
 
 def test_plan_choice_reports_the_kernels_of_the_five_workloads():

@@ -57,7 +57,8 @@ CASES = [
     ((8, 400003, 1, "f32", True), (8, 9001, 1, "f32", True)),            # a single update: step-by-step kernel
     ((12, 250001, 16, "bf16", False), (5, 1025, 3, "bf16", False)),      # no norms: nothing but the update
     ((8, 17 * 1024 * 1024 + 5, 6, "f32", True), (8, 16 * 1024 * 1024 + 1027, 6, "f32", False)),     # tiles from the queue
-    ((32, 150001, 6, "f32", True), (20, 33333, 5, "f32", True)),         # wide fp32 rows: collapsed update, direct norms
+    ((32, 150001, 8, "f32", True), (20, 33333, 7, "f32", True)),         # wide fp32 rows: collapsed update, direct norms
+    ((32, 150001, 3, "f32", True), (20, 33333, 2, "f32", True)),         # the same rows, very short streams: literal kernel
     ((32, 150001, 20, "f32", True), (20, 33333, 16, "f32", True)),       # the same rows, longer streams: matrix cores
 ]
 
@@ -70,7 +71,8 @@ def test_noalloc_matches_group_update_two_calls_in_a_row(first, second):
         (ref, got), (_, offs, mem, st, _, _, hp) = _both(W, P, U, dtype, norms, rng)
         if dtype == "f32" and W > 16 and norms:   # which of the two routes of wide fp32 rows the case exercises
             c = star.star_plan_choice(P, W, dtype, star.UpdateStream(offs, mem, st), want_norms=True, **hp)
-            assert c["kernel"] == (star.KERNEL_SEQ if U <= 6 else star.KERNEL_AFFINE_MFMA) and c["collapsed_update"] == 1
+            want = (star.KERNEL_SEQ, 0) if U <= 3 else ((star.KERNEL_SEQ, 1) if U <= 8 else (star.KERNEL_AFFINE_MFMA, 1))
+            assert (c["kernel"], c["collapsed_update"]) == want
         assert torch.equal(ref[0], got[0]) and torch.equal(ref[1], got[1])
         if norms:
             a, b = ref[2].cpu().numpy(), got[2].cpu().numpy()
