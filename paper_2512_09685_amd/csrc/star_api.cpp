@@ -535,7 +535,10 @@ star_status run(bool update, float* params, float* momentum, const void* const* 
             a.publish_dtype = publish_dtype;
             a.partials = partials;
             a.queue = want_queue ? queue : nullptr;
-            const bool mfma = how.mfma;
+            // (fp32 buffers that are not 16-byte aligned go one element per lane, and a matrix-core tile of 256
+            // elements costs what one of 1024 does: up to 16 rows the vector-register form is faster there,
+            // 32 Mi elements, 16 rows: 0.66 against 1.10 ms; with bf16 rows it is the other way round)
+            const bool mfma = how.mfma && !(!vec_ok && grad_dtype == STAR_F32 && Wp <= star::kMaxValuGramW);
             if (mfma) a.queue = queue;   // that kernel always takes its tiles from the queue
             e = mfma ? star::launch_affine_mfma(Wp, grad_dtype, update, a, num_cu, grid_cap, &grid, stream)
                      : star::launch_affine(Wp, grad_dtype, update, gram, a, num_cu, grid_cap, &grid, stream);

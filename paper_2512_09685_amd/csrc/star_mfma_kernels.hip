@@ -371,7 +371,9 @@ hipError_t launch_mfma_t(const AffArgs& a, int num_cu, int grid_cap, int* grid_o
     if (!a.queue) return hipErrorInvalidValue;
     const Geometry g = queue_geometry(num_cu, grid_cap, per_cu, kRowBytes + (UPDATE ? 32 : 0),
                                       UPDATE ? Traffic::Update : Traffic::ReadOnly,
-                                      a.vec_ok ? (a.P / 4 + kBlock - 1) / kBlock : 0);
+                                      // (buffers that are not 16-byte aligned go through the one-element path,
+                                      // which is spread over the whole grid: no tile count, no short-shard form)
+                                      a.vec_ok ? (a.P / 4 + kBlock - 1) / kBlock : -1);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), 0, s, a.params, a.momentum, a.rows, a.cf, a.P, a.vec_ok,
                        g.span_g, g.span_k, a.publish, a.publish_dtype == STAR_BF16 ? 1 : 0, a.partials, a.queue,

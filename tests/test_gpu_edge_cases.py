@@ -222,6 +222,46 @@ def test_direct_norms_option_on_anticorrelated_rows(dt):
     assert np.max(np.abs(n.cpu().numpy() - en) / en) <= 1e-6
 
 
+@pytest.mark.parametrize("dt,W,norms", [("f32", 16, True), ("bf16", 16, True), ("f32", 8, False), ("f32", 24, True)])
+def test_unaligned_buffers_keep_the_whole_grid(dt, W, norms):
+    """Views that start one element into their allocations are not 16-byte aligned and go through the
+    one-element-per-lane path.  That path is slower than the vector one but must stay within a small factor
+    of it (a launch that hands the whole shard to a single workgroup is hundreds of times slower), and its
+    results are the same as those of the aligned call on the same values."""
+    import time
+    rng = np.random.default_rng(47)
+    P = 4 << 20
+    big = [torch.from_numpy((rng.standard_normal(P + 8) * 1e-2).astype(np.float32)).cuda() for _ in range(W)]
+    if dt == "bf16":
+        big = [r.to(torch.bfloat16) for r in big]
+    offs, mem, st = rand_stream(rng, W, 8, stale=3)
+    us = star.UpdateStream(offs, mem, st)
+    p0 = torch.from_numpy((rng.standard_normal(P + 8) * 0.02).astype(np.float32)).cuda()
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+    took, outs = [], []
+    for off in (0, 1):
+        rows = [r[off:off + P] for r in big] if off else [r[1:1 + P].clone() for r in big]   # same values, aligned copies
+        pbuf, vbuf = p0.clone(), torch.zeros(P + 8, device="cuda")
+        p, v = (pbuf[1:1 + P], vbuf[1:1 + P]) if off else (pbuf[1:1 + P].clone(), vbuf[1:1 + P].clone())
+        assert (p.data_ptr() % 16 != 0) == bool(off)
+        n = torch.zeros(us.U, device="cuda") if norms else None
+        star.star_group_update(p, v, rows, us, norms_out=n, **opts(), **hp)      # warm-up; also the result compared below
+        torch.cuda.synchronize()
+        outs.append((p.clone(), v.clone(), None if n is None else n.clone()))
+        t0 = time.perf_counter()
+        for _ in range(5):
+            star.star_group_update(p, v, rows, us, norms_out=n, **opts(), **hp)
+        torch.cuda.synchronize()
+        took.append((time.perf_counter() - t0) / 5)
+    print(f"unaligned {dt} W={W} norms={norms}: aligned {took[0] * 1e6:.0f} us, one element off {took[1] * 1e6:.0f} us", flush=True)
+    assert took[1] <= 8 * took[0] + 200e-6
+    a, b = outs
+    assert so.max_rel_err(b[0].cpu().numpy(), a[0].cpu().numpy()) <= 2e-6
+    assert so.max_rel_err(b[1].cpu().numpy(), a[1].cpu().numpy()) <= 2e-6
+    if norms:
+        assert np.max(np.abs(b[2].cpu().numpy() - a[2].cpu().numpy()) / a[2].cpu().numpy()) <= 2e-6
+
+
 def test_two_threads_with_different_options():
     """Two host threads call the library at the same time with different per-call options (one forces
     the step-by-step kernel and the queue, the other the collapsed kernel and the fixed assignment);
