@@ -230,6 +230,39 @@ def test_unreferenced_rows_may_be_null():
         check(p, v, n, ep, ev, en, "f32", f"null rows kern={kern}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rows_marshalled_once_give_the_same_bits(dtype):
+    """GradRows (the rows' pointers marshalled once, for callers that reuse their buffers) against the plain
+    list of tensors: the same call, so the same bits, for every entry point that takes rows; unused rows may
+    be None in it too; a shard length that does not match is refused."""
+    rng = np.random.default_rng(21)
+    W, P, U = 6, 70001, 5
+    rows_np = rand_rows(rng, W, P, dtype)
+    offs, mem, st = rand_stream(rng, W, U, stale=3)
+    us = star.UpdateStream(offs, mem, st)
+    drows = to_dev_rows(rows_np)
+    used = set(int(x) for x in mem)
+    sparse = [r if w in used else None for w, r in enumerate(drows)]
+    held = star.GradRows(sparse)
+    assert len(held) == W and held.P == P
+    hp = dict(lr=0.05, momentum_coef=0.9, weight_decay=1e-3, wmode="stale")
+    res = []
+    for r in (drows, held):
+        p = torch.from_numpy((np.arange(P) % 7 * 0.01).astype(np.float32)).cuda()
+        v = torch.zeros(P, device="cuda")
+        n, n2, nr = torch.zeros(U, device="cuda"), torch.zeros(U, device="cuda"), torch.zeros(U, device="cuda")
+        out = [torch.zeros(P, device="cuda", dtype=drows[0].dtype) for _ in range(U)]
+        star.star_group_update(p, v, r, us, norms_out=n, **opts(), **hp)
+        star.star_group_norms(r, us, n2, wmode="stale", **opts())
+        star.star_group_reduce(out, r, us, wmode="stale", norms_out=nr, **opts())
+        torch.cuda.synchronize()
+        res.append([p, v, n, n2, nr] + out)
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    with pytest.raises(ValueError):
+        star.star_group_update(torch.zeros(P + 1, device="cuda"), torch.zeros(P + 1, device="cuda"), held, us, **hp)
+
+
 def test_empty_cases_on_device():
     p = torch.ones(16, device="cuda")
     v = torch.ones(16, device="cuda")
