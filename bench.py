@@ -103,7 +103,8 @@ def measure(wl, steps, warmup, torch, star, workloads, op="update"):
     p = workloads.make_params(wl, 0, dev)
     v = workloads.make_momentum(wl, dev)
     nsets = wl.calls if wl.fresh_grads_per_call else 1
-    sets = [workloads.make_grad_rows(wl, 0, c, dev) for c in range(nsets)]
+    # the rows' pointers are marshalled once, as a server does that receives its reports in fixed buffers
+    sets = [star.GradRows(workloads.make_grad_rows(wl, 0, c, dev)) for c in range(nsets)]
     streams = []
     for c in range(wl.calls):
         s = workloads.make_update_stream(wl, 0, c)
