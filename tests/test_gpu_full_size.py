@@ -188,6 +188,42 @@ def test_long_shard_of_wide_fp32_rows(norms):
         assert e_n <= 1e-6
 
 
+@pytest.mark.parametrize("dt,W,P", [("bf16", 8, 6 * 1024 * 1024 + 1027), ("f32", 16, 2 * 1024 * 1024 + 5),
+                                    ("bf16", 32, 12 * 1024 * 1024 + 77), ("f32", 12, 9 * 1024 * 1024 + 3)])
+def test_mid_size_shards_in_the_even_split(dt, W, P):
+    """Shards of 2 to 12 Mi elements, where the matrix-core kernel splits its tiles evenly over the workgroups
+    (up to 8 or 16 tiles each for an update, up to 48 or 128 for the norms alone) or has just gone over to
+    claims: update with norms on one element of every block of 512 plus both ends, and every norm -- of the
+    update and of star_group_norms -- against the oracle over the whole shard."""
+    import dataclasses
+    wl = dataclasses.replace(workloads.WORKLOADS["bert_base"].scaled(P), W=W, U=12, grad_dtype=dt, heavy_frac=0.0, norms=True)
+    rng = np.random.default_rng(17)
+    idx = sample_indices(wl.P, rng)
+    idx_dev = torch.from_numpy(idx).cuda()
+    p = workloads.make_params(wl, 0, "cuda")
+    v = workloads.make_momentum(wl, "cuda")
+    rows = workloads.make_grad_rows(wl, 0, 0, "cuda")
+    s = workloads.make_update_stream(wl, 0, 0)
+    us = star.UpdateStream(s["offsets"], s["members"], s["staleness"])
+    hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
+    c = star.star_plan_choice(wl.P, wl.W, dt, us, want_norms=True, **hp)
+    assert c["kernel"] == star.KERNEL_AFFINE_MFMA and c["queue_order"] == 1
+    ep, ev = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
+    n, n2 = torch.zeros(wl.U, device="cuda"), torch.zeros(wl.U, device="cuda")
+    star.star_group_update(p, v, rows, us, norms_out=n, **hp)
+    star.star_group_norms(rows, us, n2, wmode=wl.wmode, kernel=star.KERNEL_AFFINE_MFMA)
+    torch.cuda.synchronize()
+    ep, ev, _ = so.group_update(ep, ev, rows_at(rows, idx_dev), s["offsets"], s["members"], staleness=s["staleness"], **hp)
+    e_p, e_v = so.max_rel_err(p[idx_dev].cpu().numpy(), ep), so.max_rel_err(v[idx_dev].cpu().numpy(), ev)
+    en = oracle_norms([to_host(r) for r in rows], s, wl.wmode, np.arange(wl.U))
+    e_n = float(np.max(np.abs(n.cpu().numpy() - en) / en))
+    e_n2 = float(np.max(np.abs(n2.cpu().numpy() - en) / en))
+    print(f"mid-size {dt} W={W} P={P}: {idx.size} elements, err params {e_p:.3g} momentum {e_v:.3g} norms {e_n:.3g} / alone {e_n2:.3g}",
+          flush=True)
+    tol = TOL[dt]
+    assert e_p <= tol and e_v <= tol and e_n <= 1e-6 and e_n2 <= 1e-6
+
+
 @pytest.mark.parametrize("name", ["bert_base", "vgg16"])
 def test_full_size_publish_and_reduce(name):
     """The widened entry points at full workload size, on one element of every block of 512: update with a
