@@ -7,6 +7,9 @@ import torch
 import paper_2512_09685_amd as star
 
 TOL = {"f32": 1e-6, "bf16": 4e-3}   # max |x-ref| / (|ref| + RMS(ref)), per gradient dtype
+# Both sides read a bf16 row as the same bits and compute in fp32 / fp64 from there, so the bf16 cases in fact
+# hold a bound of the fp32 kind; the parity checks assert it besides the stated one.
+TOL_BF16_OBSERVED = 3e-6
 
 
 _TILE_ORDER = {"queue_threshold": None}

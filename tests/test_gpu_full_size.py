@@ -23,7 +23,7 @@ import torch
 import paper_2512_09685_amd as star
 import workloads
 from oracle import star_oracle as so
-from gpu_util import TOL
+from gpu_util import TOL, TOL_BF16_OBSERVED
 
 pytestmark = pytest.mark.gpu
 
@@ -102,7 +102,7 @@ def test_full_size_workload(name):
     whole = name in WHOLE
     ep, ev = (p.cpu().numpy(), v.cpu().numpy()) if whole else (p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy())
     hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
-    tol = TOL[wl.grad_dtype]
+    tol = min(TOL[wl.grad_dtype], TOL_BF16_OBSERVED)
     choice = None
     rows = None
     for call in range(wl.calls):
@@ -220,7 +220,7 @@ def test_mid_size_shards_in_the_even_split(dt, W, P):
     e_n2 = float(np.max(np.abs(n2.cpu().numpy() - en) / en))
     print(f"mid-size {dt} W={W} P={P}: {idx.size} elements, err params {e_p:.3g} momentum {e_v:.3g} norms {e_n:.3g} / alone {e_n2:.3g}",
           flush=True)
-    tol = TOL[dt]
+    tol = min(TOL[dt], TOL_BF16_OBSERVED)
     assert e_p <= tol and e_v <= tol and e_n <= 1e-6 and e_n2 <= 1e-6
 
 
@@ -246,7 +246,7 @@ def test_full_size_publish_and_reduce(name):
     torch.cuda.synchronize()
     sub = rows_at(rows, idx_dev)
     ep, ev, _ = so.group_update(p0, v0, sub, s["offsets"], s["members"], staleness=s["staleness"], **hp)
-    tol = TOL[wl.grad_dtype]
+    tol = min(TOL[wl.grad_dtype], TOL_BF16_OBSERVED)
     assert so.max_rel_err(p[idx_dev].cpu().numpy(), ep) <= tol
     assert so.max_rel_err(v[idx_dev].cpu().numpy(), ev) <= tol
     assert torch.equal(pub.float(), p.to(torch.bfloat16).float())       # the whole copy: RNE of the new params
@@ -291,7 +291,7 @@ def test_full_size_single_update(name):
     st = None if s["staleness"] is None else np.asarray(s["staleness"][:hi], np.int32)
     print(f"full-size single update {name}: P={wl.P} group of {hi} of {wl.W} workers", flush=True)
     hp = dict(lr=wl.lr, momentum_coef=wl.momentum, weight_decay=wl.weight_decay, wmode=wl.wmode)
-    tol = TOL[wl.grad_dtype]
+    tol = min(TOL[wl.grad_dtype], TOL_BF16_OBSERVED)
     ep, ev = p[idx_dev].cpu().numpy(), v[idx_dev].cpu().numpy()
     norms = torch.zeros(1, device="cuda")
     for call in range(2):                                   # twice: the second call starts from the first's state

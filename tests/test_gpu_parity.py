@@ -8,7 +8,7 @@ import torch
 import paper_2512_09685_amd as star
 import workloads
 from oracle import star_oracle as so
-from gpu_util import TOL, gpu_update, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
+from gpu_util import TOL, TOL_BF16_OBSERVED, gpu_update, opts, rand_rows, rand_stream, tile_order, to_dev_rows  # noqa: F401 (tile_order: autouse fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -17,7 +17,7 @@ KERNELS = {"auto": star.KERNEL_AUTO, "seq": star.KERNEL_SEQ, "affine": star.KERN
 
 
 def check(p, v, n, ep, ev, en, dtype, what=""):
-    tol = TOL[dtype]
+    tol = min(TOL[dtype], TOL_BF16_OBSERVED)
     e_p, e_v = so.max_rel_err(p, ep), so.max_rel_err(v, ev)
     print(f"[{what}] err p={e_p:.3g} v={e_v:.3g}", end="")
     assert e_p <= tol and e_v <= tol, (what, e_p, e_v)
