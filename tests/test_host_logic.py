@@ -478,3 +478,48 @@ def test_host_planner_and_selector_under_sanitizers(tmp_path):
     r = subprocess.run([str(exe), "20000", "10000"], capture_output=True, text=True)
     assert r.returncode == 0, (r.stdout, r.stderr[-2000:])
     assert "plans accepted" in r.stdout and "selector calls accepted 20000" in r.stdout
+
+
+def test_plan_choice_is_consistent_over_random_calls():
+    """star_plan_choice over a few thousand random calls (streams, row counts, dtypes, shard lengths, norms,
+    weightings with and without negative coefficients, options): whatever rule fires, the answer hangs together."""
+    rng = np.random.default_rng(2024)
+    seen = set()
+    for _ in range(4000):
+        W = int(rng.integers(1, 33))
+        U = int(rng.choice([1, 2, 3, 4, 8, 16, 40, 200]))
+        offs, mem, _ = _rand_stream(rng, W, U)
+        explicit = rng.random() < 0.2
+        cf = (rng.uniform(-1 if rng.random() < 0.5 else 0.01, 1, len(mem)).astype(np.float32)) if explicit else None
+        us = star.UpdateStream(offs, mem, None, cf)
+        P = int(rng.choice([1, 1000, 1 << 18, 1 << 20, 3 << 20, 5 << 20, 9 << 20, 17 << 20, 40 << 20, 70 << 20, 300 << 20]))
+        dt = str(rng.choice(["f32", "bf16"]))
+        update, norms = bool(rng.random() < 0.8), bool(rng.random() < 0.6)
+        if not update:
+            norms = True
+        kw = dict(update=update, want_norms=norms, wmode="explicit" if explicit else "mean",
+                  kernel=None if rng.random() < 0.7 else int(rng.integers(0, 4)),
+                  queue_threshold=None if rng.random() < 0.8 else int(rng.choice([1, 1 << 40])),
+                  direct_norms=bool(rng.random() < 0.15))
+        c = star.star_plan_choice(P, W, dt, us, lr=0.1, momentum_coef=0.9, **kw)
+        used = len(set(int(x) for x in mem))
+        assert c["kernel"] in (star.KERNEL_SEQ, star.KERNEL_AFFINE, star.KERNEL_AFFINE_MFMA), (kw, c)
+        assert c["rows_used"] == used and used <= c["rows_padded"] <= 32
+        assert c["launches"] >= 1 and c["queue_order"] in (0, 1) and c["collapsed_update"] in (0, 1)
+        assert (c["finishing_launches"] > 0) == norms, (kw, c)
+        if c["kernel"] == star.KERNEL_AFFINE_MFMA:
+            assert norms and c["queue_order"] == 1 and c["finishing_launches"] == 2
+        if c["kernel"] == star.KERNEL_AFFINE:
+            assert c["collapsed_update"] == (1 if update else 0)
+            if norms and c["rows_padded"] > 16:      # no vector-register Gram beyond 16 rows: update plus a direct norm pass
+                assert update and c["launches"] >= 2
+        if c["kernel"] != star.KERNEL_SEQ and not update:
+            assert c["launches"] == 1
+        if not update:
+            assert c["collapsed_update"] == 0
+        if kw["kernel"] in (star.KERNEL_SEQ, star.KERNEL_AFFINE_MFMA) and (norms or kw["kernel"] == star.KERNEL_SEQ):
+            assert c["kernel"] == kw["kernel"], (kw, c)
+        if kw["queue_threshold"] == 1 << 40 and c["kernel"] != star.KERNEL_AFFINE_MFMA:
+            assert c["queue_order"] == 0
+        seen.add((c["kernel"], c["collapsed_update"], c["queue_order"], c["launches"] > 1))
+    assert len(seen) >= 8       # the generator reaches the different routes
