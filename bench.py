@@ -35,7 +35,7 @@ def kernel_source_digest():
     import re
     csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2512_09685_amd", "csrc")
     h = hashlib.sha256()
-    for name in ("star_kernels.hip", "star_mfma_kernels.hip", "star_device.h"):
+    for name in ("star_kernels.hip", "star_mfma_kernels.hip", "star_reduce_kernels.hip", "star_device.h", "star_kernels.h"):
         text = open(os.path.join(csrc, name), "r").read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         text = re.sub(r"//[^\n]*", "", text)

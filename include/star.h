@@ -186,7 +186,9 @@ typedef struct {
  * cancels (measured at kappa = 4e4: 2.6e-6 with the vector-register Gram
  * matrix, 1.8e-5 with the matrix-core one).  With coefficients of both signs (STAR_W_EXPLICIT) the library
  * therefore takes the norms from direct sums of gbar_u^2 in a pass of its
- * own (error 1e-6 or less, one more read of the rows); star_options.flags =
+ * own (error 1e-6 or less, one more read of the rows), and so it does on
+ * shards of fewer than 4096 elements, where a group's sum over so few
+ * elements cancels as a matter of course; star_options.flags =
  * STAR_OPT_DIRECT_NORMS asks for the same on any stream (the update stays the
  * collapsed one), and star_options.kernel = STAR_KERNEL_SEQ evaluates update
  * and norms step by step.

@@ -307,7 +307,11 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
     // rows).  Unless the caller forces an evaluation, such streams get their norms from the direct sums
     // of gbar^2 (step-by-step kernel, norms only), in a pass of its own beside the collapsed update; so
     // does any stream whose caller asks for it (STAR_OPT_DIRECT_NORMS).
-    if (want_norms && (plan.negative_coef || opt.direct_norms) && opt.kernel == STAR_KERNEL_AUTO &&
+    // So does a shard of a few thousand elements: the sum of a handful of elements' signed values cancels as a
+    // matter of course (one element, 16 rows: kappa of 1000 is ordinary), the concentration that keeps kappa
+    // near y_u needs dimension, and at that length the cost is a launch, not bandwidth.
+    const bool tiny = P < star::kTinyShardElements;
+    if (want_norms && (plan.negative_coef || opt.direct_norms || tiny) && opt.kernel == STAR_KERNEL_AUTO &&
         l.route == star::Route::Affine) {
         if (update) l.split_norms = true;
         else l.route = star::Route::Seq;

@@ -59,6 +59,8 @@ inline int queue_claim(int thread_bytes, Traffic traffic = Traffic::Update) {
 // per workgroup the claims' round trips show (1 Mi elements: 15 against 7.5 us); from 16 Mi on the
 // queue order wins (+12 % with 8 fp32 rows).
 constexpr int64_t kQueueMinElements = 16 << 20;
+// Shards shorter than this take their norms from direct sums whatever the stream (see decide()).
+constexpr int64_t kTinyShardElements = 4096;
 
 // First round of claims (see for_each_claimed_tile): workgroup b of G gets 1 + b % claim tiles, laid out
 // one after the other from tile 0; the queue's counter hands out the tiles from `base` on.

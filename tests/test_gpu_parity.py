@@ -53,6 +53,50 @@ def test_random_shapes(dtype, kname, W, P, U, norms):
     check(p, v, n, ep, ev, en, dtype, f"{kname} W={W} P={P} U={U}")
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_calls_whatever_the_library_chooses(seed):
+    """Random calls -- row count, stream length, group sizes, dtype, shard length up to 2.5 Mi elements, weighting,
+    norms, the direct-norms flag, either entry point -- with the library left to choose its kernels: whichever
+    of its rules fires (literal kernel for very short streams, vector-register or matrix-core Gram, even split,
+    direct norm pass, collapsed update with the norm walk), the result is the oracle's."""
+    rng = np.random.default_rng(5000 + seed)
+    for case in range(12):
+        W = int(rng.choice([1, 2, 3, 5, 6, 7, 8, 9, 12, 16, 17, 24, 32]))
+        U = int(rng.choice([1, 2, 3, 4, 6, 10, 24]))
+        P = int(rng.choice([1, 77, 4099, 70001, 300007, 1300003, 2500001]))
+        if P > 1000000 and W * U > 200:
+            P = 300007                    # keeps the oracle's share of the test at seconds
+        dtype = str(rng.choice(["f32", "bf16"]))
+        norms = bool(rng.random() < 0.7)
+        wmode = str(rng.choice(["mean", "stale", "explicit"]))
+        rows = rand_rows(rng, W, P, dtype)
+        offs, mem, st = rand_stream(rng, W, U, max_y=int(rng.integers(1, W + 1)), stale=3)
+        cf = None
+        if wmode == "explicit":
+            cf = rng.uniform(0.05, 1.0, len(mem)).astype(np.float32)
+        hp = dict(lr=0.05, momentum_coef=float(rng.choice([0.0, 0.9])), weight_decay=float(rng.choice([0.0, 1e-3])),
+                  wmode=wmode, scale_lr_by_group=bool(rng.random() < 0.3))
+        stale = st if wmode == "stale" else None
+        p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+        v0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+        direct = bool(norms and rng.random() < 0.25)
+        noalloc = bool(rng.random() < 0.3)
+        us = star.UpdateStream(offs, mem, stale, cf)
+        c = star.star_plan_choice(P, W, dtype, us, want_norms=norms, direct_norms=direct, **hp)
+        what = (f"seed {seed} case {case}: W={W} U={U} P={P} {dtype} norms={norms} {wmode} direct={direct} noalloc={noalloc} "
+                f"-> kernel {c['kernel']} collapsed {c['collapsed_update']} launches {c['launches']}")
+        print(what, flush=True)
+        ep, ev, en = so.group_update(p0, v0, rows, offs, mem, staleness=stale, coeff=cf, want_norms=norms, **hp)
+        p, v = torch.from_numpy(p0).cuda(), torch.from_numpy(v0).cuda()
+        n = torch.full((U,), -1.0, device="cuda") if norms else None
+        if noalloc:
+            star.star_group_update_noalloc(p, v, to_dev_rows(rows), us, norms_out=n, **hp)
+        else:
+            star.star_group_update(p, v, to_dev_rows(rows), us, norms_out=n, direct_norms=direct, **opts(), **hp)
+        torch.cuda.synchronize()
+        check(p.cpu().numpy(), v.cpu().numpy(), None if n is None else n.cpu().numpy(), ep, ev, en, dtype, what)
+
+
 @pytest.mark.parametrize("name", workloads.ORDER)
 @pytest.mark.parametrize("kname", ["seq", "auto"])
 def test_workload_structure_scaled_down(name, kname):

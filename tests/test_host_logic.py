@@ -187,13 +187,19 @@ def test_plan_choice_one_update_is_literal_many_are_collapsed():
     rng = np.random.default_rng(0)
     offs, mem, _ = _rand_stream(rng, 16, 64)
     many = star.UpdateStream(offs, mem)
-    c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True)
+    c = star.star_plan_choice(100000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True)
     assert c["kernel"] == star.KERNEL_AFFINE_MFMA and c["fma_affine"] == 36 + 136 and c["fma_seq"] == len(mem) + 4 * 64
     assert c["queue_order"] == 1 and c["finishing_launches"] == 2      # the matrix-core kernel always takes the queue
     c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True, kernel=star.KERNEL_AFFINE)
     assert c["kernel"] == star.KERNEL_AFFINE and c["queue_order"] == 0
     c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True, kernel=star.KERNEL_SEQ)
     assert c["kernel"] == star.KERNEL_SEQ and c["launches"] == 3 and c["finishing_launches"] == 3 and c["tables_inline"] == 0
+    # a shard of fewer than 4096 elements: norms from direct sums whatever the stream (a pass of its own beside the
+    # collapsed update; the step-by-step kernel for the norms alone)
+    c = star.star_plan_choice(1000, 16, "f32", many, lr=0.1, momentum_coef=0.9, want_norms=True)
+    assert c["kernel"] == star.KERNEL_AFFINE and c["collapsed_update"] == 1 and c["launches"] == 1 + 3
+    assert star.star_plan_choice(1000, 16, "f32", many, update=False, want_norms=True)["kernel"] == star.KERNEL_SEQ
+    assert star.star_plan_choice(4096, 16, "f32", many, update=False, want_norms=True)["kernel"] == star.KERNEL_AFFINE_MFMA
 
 
 def test_plan_choice_wide_fp32_rows_with_norms():
