@@ -242,44 +242,53 @@ size_t partial_doubles_needed(int Wp, int U, int grid_cap) {
     return std::max(ng, useq) * (size_t)grid_cap + ng;
 }
 
-// Where the Gram matrix behind the norms is formed.  On the matrix cores, except for up to 6 rows: the
-// matrix instructions cost the same for 1 row as for 16 (fp32: 64 per wave and tile, about 0.85 us),
-// which a tile of few rows does not hide, while the vector-register form needs only W(W+1)/2 <= 21
-// accumulators there and takes its tiles from the queue as well (norms on, 8 updates: 1 fp32 row 0.34
-// against 0.49 ms on 100 M elements, 4 rows 0.53 against 0.64; 1 bf16 row 0.59 against 0.66 ms on 200 M
-// elements; 6 rows equal, 7 and 8 rows 2-6 % behind).
-// Without the update (norms alone, the Gram matrix alone) the rule is a different one, see the function.
-// On shards below 16 Mi elements an update with norms on 7 or 8 rows is faster with the vector-register form and
-// its fixed assignment as well (36 accumulators still leave room): 1 Mi elements 21 against 28 us, 8 Mi 80
-// against 89 us, equal at 16 Mi; 16 rows are faster on the matrix cores at every length.
-// 3 to 8 bf16 rows are the exception to the exception: up to 8 Mi elements the matrix-core kernel splits its
-// tiles evenly over the workgroups instead of claiming them (queue_geometry), and with tiles that light it is
-// then 5-16 % ahead of the vector-register form (6 rows: 2 / 4 / 8 Mi elements 20 / 30 / 50 against 24 / 36 / 60 us);
-// 5 and 6 rows keep that lead until the vector-register form takes the queue at 48 Mi elements (6 rows, 16 / 32 / 40 Mi:
-// 95 / 172 / 211 against 106 / 197 / 244 us; equal from 48 Mi on), 4 rows have it again from 16 Mi on (32 Mi: 153
-// against 160 us; at 12 Mi the vector-register form is 4 % ahead).
+// Where the Gram matrix behind the norms is formed: on the matrix cores (aff_mfma_kernel) or in vector
+// registers (aff_kernel, up to kMaxValuGramW rows).  The matrix instructions cost the same for 1 row as for 16
+// (fp32: 64 per wave and tile, about 0.85 us), which a tile of few rows does not hide; the vector-register form
+// needs W(W+1)/2 accumulators, 21 for 6 rows, 136 for 16.  Every limit below is a measured crossover of the two
+// forms on MI355X (256 compute units), both forced through star_options.kernel on the same inputs;
+// tests/test_host_logic.py pins the table.
 bool gram_on_matrix_cores(int Wp, int grad_dtype, int choice, bool update, int64_t P) {
     if (Wp > star::kMaxValuGramW) return true;
     if (choice == STAR_KERNEL_AFFINE) return false;
     if (choice == STAR_KERNEL_AFFINE_MFMA) return true;
+    const bool f32 = grad_dtype == STAR_F32;
+    constexpr int64_t Mi = 1 << 20;
     if (!update) {
-        // norms or Gram matrix alone (a pure read).  fp32 rows: up to 8 on the vector ALUs, whose long-lived
-        // workgroups with a fixed assignment reach 0.80-0.88 of the HBM peak there, while the matrix instructions
-        // cost as much for 7 rows as for 16 (96 Mi elements, 7 / 8 rows: 400 / 458 against 497 / 545 us; 12 rows
-        // equal).  bf16 rows: the light tiles of 3 to 6 rows are faster on the matrix-core kernel while it splits
-        // its tiles evenly (12 Mi elements, 3 / 4 / 6 rows: 30 / 31 / 34 against 39 / 44 / 54 us) and slower on
-        // long shards, where the vector-register form loads several chunks per thread (96 Mi elements, 4 / 5 / 6
-        // rows: 141 / 167 / 201 against 182 / 197 / 211 us); from 7 rows on the matrix cores at every length.
-        if (grad_dtype == STAR_F32) return Wp > 8;
+        // Norms or Gram matrix alone: a pure read.
+        // fp32 rows: up to 8 on the vector ALUs, whose long-lived workgroups with a fixed assignment reach 0.80-0.88
+        // of the HBM peak there (96 Mi elements, 7 / 8 rows: 400 / 458 against 497 / 545 us; 12 rows equal).
+        if (f32) return Wp > 8;
+        // bf16 rows: from 7 rows on the matrix cores at every length.  The light tiles of 3 to 6 rows are faster
+        // there while that kernel splits its tiles evenly (12 Mi elements, 3 / 4 / 6 rows: 30 / 31 / 34 against
+        // 39 / 44 / 54 us) and slower on long shards, where the vector-register form loads several chunks per
+        // thread (96 Mi elements, 4 / 5 / 6 rows: 141 / 167 / 201 against 182 / 197 / 211 us).
         if (Wp >= 7) return true;
-        if (Wp >= 5) return P <= (48 << 20);
-        if (Wp >= 3) return P <= (16 << 20);
+        if (Wp >= 5) return P <= 48 * Mi;
+        if (Wp >= 3) return P <= 16 * Mi;
         return false;
     }
-    if (update && grad_dtype == STAR_BF16 && Wp >= 3 && Wp <= 8 && P <= (8 << 20)) return true;
-    if (update && grad_dtype == STAR_BF16 && Wp >= 4 && Wp <= 6 && P < 3 * star::kQueueMinElements)
-        return Wp >= 5 || P >= (16 << 20);
-    if (update && Wp <= 8 && P < star::kQueueMinElements) return false;
+    // Update with norms.
+    // Up to 6 rows the vector-register form, which with so few accumulators takes its tiles from the queue as well
+    // (8 updates: 1 fp32 row 0.34 against 0.49 ms on 100 M elements, 4 rows 0.53 against 0.64; 1 bf16 row 0.59
+    // against 0.66 ms on 200 M elements; 6 rows equal); from 7 rows on the matrix cores (7 and 8 rows: 2-6 % ahead
+    // on long shards, 16 rows ahead at every length).  Two refinements on shorter shards:
+    //  - fp32 rows, 7 or 8 of them, below 16 Mi elements: the vector-register form with its fixed assignment
+    //    (1 Mi elements 21 against 28 us, 8 Mi 80 against 89 us, equal at 16 Mi);
+    //  - bf16 rows, 3 to 8 of them: the matrix-core kernel up to 8 Mi elements, where it splits its tiles evenly over
+    //    the workgroups (queue_geometry) and with tiles that light is 5-16 % ahead (6 rows, 2 / 4 / 8 Mi elements:
+    //    20 / 30 / 50 against 24 / 36 / 60 us).  5 and 6 rows keep that lead until the vector-register form takes the
+    //    queue at 48 Mi elements (6 rows, 16 / 32 / 40 Mi: 95 / 172 / 211 against 106 / 197 / 244 us; equal from 48 Mi
+    //    on); 4 rows have it from 16 Mi on (32 Mi: 153 against 160 us; at 12 Mi the vector-register form is 4 % ahead);
+    //    7 and 8 rows are level or 3 % behind between 8 and 16 Mi.
+    if (f32) {
+        if (Wp <= 8 && P < star::kQueueMinElements) return false;
+        return Wp > star::kFewRows;
+    }
+    if (Wp >= 3 && Wp <= 8 && P <= 8 * Mi) return true;
+    if (Wp >= 5 && Wp <= 6 && P < 48 * Mi) return true;
+    if (Wp == 4 && P >= 16 * Mi && P < 48 * Mi) return true;
+    if (Wp <= 8 && P < star::kQueueMinElements) return false;
     return Wp > star::kFewRows;
 }
 
