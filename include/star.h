@@ -143,7 +143,8 @@ typedef struct {
                                 workgroups that claim tiles (1024 consecutive elements of every
                                 buffer) in address order from a work queue; shorter ones get a fixed
                                 assignment, which starts faster.  0 = default (updates: 16 Mi elements
-                                with fp32 rows, 32 Mi with up to 4 of them, 48 Mi with bf16 rows; norms
+                                with fp32 rows, 64 Mi with up to 4 of them; with bf16 rows 64 Mi, 96 Mi
+                                with up to 12 of them, 128 Mi with up to 4; norms
                                 and Gram matrix alone 16 Mi; the aggregation 64 Mi, and never with up
                                 to 8 bf16 or 4 fp32 rows); 1 = always the queue; negative:
                                 STAR_ERR_SHAPE                                                          */

@@ -57,21 +57,34 @@ struct Opts {
 // 2-96 Mi elements, 16 updates, that is from about 16 Mi elements on with 8 and more fp32 rows (16 Mi: 0.76
 // against 0.66 of the HBM peak with 8 rows, equal with 16), from about 32 Mi with up to 4 fp32 rows, and from
 // about 48 Mi with bf16 rows, whose tiles are half as heavy (16-32 Mi: the fixed assignment is 0-14 % ahead,
-// 64 Mi and more: the queue 2-8 %).  Norms and Gram matrix alone keep 16 Mi (few rows, vector registers: at 8 Mi
+// 64 Mi and more: the queue 2-8 % -- with 16 rows; see below for the other row counts).  Norms and Gram matrix alone keep 16 Mi (few rows, vector registers: at 8 Mi
 // the fixed assignment is 5-25 % ahead, from 24 Mi on the queue, whose tiles hold several chunks per thread, by
 // 10 % to 4x).  The aggregation, a read of W rows with one row written, is faster with the fixed assignment far
 // longer: 4-48 Mi elements 2-25 % ahead for every row count and dtype, equal from about 96 Mi on with 16 and more
 // rows (the queue 2-3 % ahead from 96-144 Mi), and with light tiles -- up to 8 bf16 or 4 fp32 rows -- ahead at
 // every length tried (256 Mi elements, 4 / 8 bf16 rows: 480 / 808 against 622 / 876 us).
-int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update, bool aggregation = false) {
+int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update, bool aggregation = false,
+                      bool norms = false) {
     if (opt.queue_min > 0) return opt.queue_min;
     if (aggregation) {
         const int row_bytes = rows * (grad_dtype == STAR_F32 ? 16 : 8);   // per thread and tile
         return row_bytes <= 64 ? (int64_t)1 << 62 : 4 * star::kQueueMinElements;
     }
     if (!update) return star::kQueueMinElements;
-    if (grad_dtype == STAR_BF16) return 3 * star::kQueueMinElements;
-    return rows <= 4 ? 2 * star::kQueueMinElements : star::kQueueMinElements;
+    // (A second A/B of the two tile orders, 8-320 Mi elements, 1-32 rows, moved the limits of the light updates up:
+    // bf16 rows, 48-96 Mi elements: the fixed assignment 5-12 % ahead with up to 4 rows, 3-7 % with 8, level or ahead
+    // with 32, behind with 16 from 64 Mi on; up to 4 fp32 rows: ahead or level up to 64 Mi; from 128 Mi on the two
+    // orders are within 3 % of each other for every light update and the queue is kept.)
+    // With norms on up to 6 rows (the few-rows form of the vector-register Gram matrix, whose queue tiles fold
+    // their sums per chunk) the picture is another one again: bf16 rows gain 8-16 % from the queue from 16-32 Mi
+    // elements on (6 rows, 16 / 48 Mi: 96 / 246 against 106 / 290 us), one fp32 row from 32 Mi, while 3 to 6 fp32
+    // rows are 3-10 % faster with the fixed assignment up to 96 Mi (6 rows, 32 Mi: 220 against 245 us).
+    if (norms && rows <= star::kFewRows) {
+        if (grad_dtype == STAR_BF16) return star::kQueueMinElements;
+        return (rows <= 1 ? 2 : (rows <= 2 ? 4 : 8)) * star::kQueueMinElements;
+    }
+    if (grad_dtype == STAR_BF16) return (rows <= 4 ? 8 : (rows <= 12 ? 6 : 4)) * star::kQueueMinElements;
+    return rows <= 4 ? 4 * star::kQueueMinElements : star::kQueueMinElements;
 }
 
 star_status resolve_options(const star_options* o, Opts* out) {
@@ -326,7 +339,7 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
         else l.route = star::Route::Seq;
     }
     l.Wp = star::padded_rows(plan.Wc);
-    l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update);
+    l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update, false, update && want_norms);
     // Update with norms, a stream so short that walking it costs next to nothing (fma_seq, the sum of y_u + 4 over
     // the updates): the literal kernel forms its norms directly, in the same pass, and needs one finishing launch
     // where the Gram route needs two.  On a short shard that launch is most of the difference (1 Mi elements:
