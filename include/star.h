@@ -144,7 +144,8 @@ typedef struct {
                                 buffer) in address order from a work queue; shorter ones get a fixed
                                 assignment, which starts faster.  0 = default (updates: 16 Mi elements
                                 with fp32 rows, 64 Mi with up to 4 of them; with bf16 rows 64 Mi, 96 Mi
-                                with up to 12 of them, 128 Mi with up to 4; norms
+                                with up to 12 of them, 128 Mi with up to 4; updates with norms on up to
+                                6 rows: 16 Mi with bf16 rows, 32 / 64 / 128 Mi with 1 / 2 / 3-6 fp32 rows; norms
                                 and Gram matrix alone 16 Mi; the aggregation 64 Mi, and never with up
                                 to 8 bf16 or 4 fp32 rows); 1 = always the queue; negative:
                                 STAR_ERR_SHAPE                                                          */
