@@ -64,7 +64,7 @@ struct Opts {
 // rows (the queue 2-3 % ahead from 96-144 Mi), and with light tiles -- up to 8 bf16 or 4 fp32 rows -- ahead at
 // every length tried (256 Mi elements, 4 / 8 bf16 rows: 480 / 808 against 622 / 876 us).
 int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update, bool aggregation = false,
-                      bool norms = false) {
+                      bool norms = false, bool literal = false) {
     if (opt.queue_min > 0) return opt.queue_min;
     if (aggregation) {
         const int row_bytes = rows * (grad_dtype == STAR_F32 ? 16 : 8);   // per thread and tile
@@ -79,7 +79,10 @@ int64_t queue_min_for(const Opts& opt, int grad_dtype, int rows, bool update, bo
     // their sums per chunk) the picture is another one again: bf16 rows gain 8-16 % from the queue from 16-32 Mi
     // elements on (6 rows, 16 / 48 Mi: 96 / 246 against 106 / 290 us), one fp32 row from 32 Mi, while 3 to 6 fp32
     // rows are 3-10 % faster with the fixed assignment up to 96 Mi (6 rows, 32 Mi: 220 against 245 us).
+    // (The literal kernel with its direct norm sums, one or two updates: the queue from 32 Mi elements, 4 fp32 rows,
+    // 48 / 64 Mi: 272 / 356 against 300 / 400 us.)
     if (norms && rows <= star::kFewRows) {
+        if (literal) return 2 * star::kQueueMinElements;
         if (grad_dtype == STAR_BF16) return star::kQueueMinElements;
         return (rows <= 1 ? 2 : (rows <= 2 ? 4 : 8)) * star::kQueueMinElements;
     }
@@ -339,7 +342,6 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
         else l.route = star::Route::Seq;
     }
     l.Wp = star::padded_rows(plan.Wc);
-    l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update, false, update && want_norms);
     // Update with norms, a stream so short that walking it costs next to nothing (fma_seq, the sum of y_u + 4 over
     // the updates): the literal kernel forms its norms directly, in the same pass, and needs one finishing launch
     // where the Gram route needs two.  On a short shard that launch is most of the difference (1 Mi elements:
@@ -369,6 +371,8 @@ Launch decide(const star::Plan& plan, int grad_dtype, bool update, bool want_nor
         l.route = star::Route::Seq;
         l.collapsed_in_seq = true;
     }
+    l.want_queue = P >= queue_min_for(opt, grad_dtype, plan.Wc, update, false, update && want_norms,
+                                      l.route == star::Route::Seq);
     if (l.route == star::Route::Affine) {
         const bool gram = want_norms;
         l.mfma = gram && gram_on_matrix_cores(l.Wp, grad_dtype, opt.kernel, update, P);
