@@ -147,7 +147,8 @@ typedef struct {
                                 with up to 12 of them, 128 Mi with up to 4; updates with norms on up to
                                 6 rows: 16 Mi with bf16 rows, 32 / 64 / 128 Mi with 1 / 2 / 3-6 fp32 rows; norms
                                 and Gram matrix alone 16 Mi; the aggregation 64 Mi, and never with up
-                                to 8 bf16 or 4 fp32 rows); 1 = always the queue; negative:
+                                to 8 bf16 or 4 fp32 rows or with several groups of bf16 rows); 1 = always
+                                the queue; negative:
                                 STAR_ERR_SHAPE                                                          */
 } star_options;
 

@@ -149,8 +149,10 @@ hipError_t launch_reduce_t(const ReduceArgs& a, int num_cu, int grid_cap, int* g
     const bool queued = a.queue && a.vec_ok;
     const Geometry g = queued ? queue_geometry(num_cu, grid_cap, queue_workgroups_per_cu(0, false),
                                                W * (int)sizeof(typename R::vec) + 16, Traffic::Reduce)
+                              // (with norms: long-lived workgroups, and at least two of them per unit whatever
+                                              // the tile weighs -- 32 bf16 rows, 16 groups, 32 Mi elements: one per unit 1.72 ms)
                               : pick_geometry(a.P, 4, a.vec_ok != 0, a.norms != 0, num_cu, grid_cap,
-                                              W * (int)sizeof(typename R::vec), 4);
+                                              W * (int)sizeof(typename R::vec), 4, 2);
     *grid_out = g.grid;
     hipLaunchKernelGGL(kern, dim3(g.grid), dim3(kBlock), lds, s, a.rows, a.coef, a.mask, a.out, a.U,
                        a.out_dtype == STAR_BF16 ? 1 : 0, a.P, a.vec_ok, a.norms, g.span_g, g.span_k, a.partials,
